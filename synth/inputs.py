@@ -1,0 +1,173 @@
+"""Seeded, keyed synthetic inputs shaped like the paper's hBERT / hGPT serving workloads.
+
+Every array is a pure function of ``(seed, what, tenant-or-request, layer, tensor)``:
+a tenant's weights or a request's hidden states can be regenerated alone, so a
+consumer never has to materialise a whole 1 000- or 10 000-tenant pool to look at
+the few tenants a batch touches.  Values are drawn in fp32 and rounded ONCE to the
+storage dtype (bf16 or fp32); every consumer starts from those rounded values.
+
+Nothing here computes any part of the layer: only random draws, shape tables and
+dtype packing.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import List, Tuple
+
+import numpy as np
+
+BLOCK_FFN = 0          # Y = LN(X + W2 GELU(W1 X + b1) + b2)
+BLOCK_ENC_POSTLN = 1   # bidirectional attention + FFN, LayerNorm after each residual
+BLOCK_DEC_PRELN = 2    # causal attention + FFN, LayerNorm before each sub-layer
+BLOCK_ADAPTER = 3      # Y = X + Up(ReLU(Down(X)))  (bottleneck adapter, Sec. 3.2.2)
+
+_TAG_WEIGHT, _TAG_X, _TAG_IDS, _TAG_LENS = 1, 2, 3, 4
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    block: int
+    dtype: str            # "f32" | "bf16": storage dtype of weights and activations
+    d_model: int
+    d_ff: int             # FFN width (adapter: bottleneck width r)
+    n_heads: int          # 0 for blocks without attention
+    n_layers: int
+    n_tenants: int
+    n_requests: int
+    seq_min: int
+    seq_max: int          # inclusive; == seq_min for fixed-length batches
+    popularity: str       # "uniform" | "zipf"
+    zipf_s: float
+    ln_eps: float
+    hbm_slots: int        # tenants resident in HBM at once
+    host_tier: bool       # pinned-host pool + HBM cache + swap-in
+    seed: int = 0
+
+    def scaled(self, **kw) -> "Workload":
+        """Same recipe at another size (tests use reduced tenant / request counts)."""
+        return replace(self, **kw)
+
+
+# The five configurations of the target, by name.  Sequence length 128 is the paper's
+# throughput setting (Sec. 7.2); up to 10 000 tenants is its scale claim (Sec. 7.1).
+WORKLOADS = {
+    "tiny_fp32": Workload("tiny_fp32", BLOCK_FFN, "f32", 64, 256, 0, 1, 4, 8, 16, 16,
+                          "uniform", 0.0, 1e-12, 4, False),
+    "bert_ffn": Workload("bert_ffn", BLOCK_FFN, "bf16", 768, 3072, 0, 1, 64, 256, 128, 128,
+                         "uniform", 0.0, 1e-12, 64, False),
+    "hbert_enc2": Workload("hbert_enc2", BLOCK_ENC_POSTLN, "bf16", 768, 3072, 12, 2, 1000, 512,
+                           128, 128, "zipf", 1.1, 1e-12, 1000, False),
+    "hgpt_dec": Workload("hgpt_dec", BLOCK_DEC_PRELN, "bf16", 1024, 4096, 16, 1, 2000, 256,
+                         32, 512, "zipf", 1.0, 1e-5, 2000, False),
+    "hbert_10k": Workload("hbert_10k", BLOCK_ENC_POSTLN, "bf16", 768, 3072, 12, 1, 10000, 1024,
+                          16, 256, "zipf", 0.8, 1e-12, 2000, True),
+    # Paper-exact bottleneck adapter (Sec. 3.2.2); rank 64 is this build's reading.
+    "hbert_adapter": Workload("hbert_adapter", BLOCK_ADAPTER, "bf16", 768, 64, 0, 1, 1000, 512,
+                              128, 128, "zipf", 1.1, 0.0, 1000, False),
+}
+
+
+def tensor_specs(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
+    """Canonical tensor order of one (tenant, layer) image: (name, shape, kind).
+
+    Matrices are ``[out, in]`` row-major (Linear(a) = W a + b, Sec. 3.2.2).
+    kind: "w" weight, "b" bias, "g" LayerNorm gain, "beta" LayerNorm shift.
+    """
+    d, f = wl.d_model, wl.d_ff
+    ffn = [("w1", (f, d), "w"), ("b1", (f,), "b"), ("w2", (d, f), "w"), ("b2", (d,), "b")]
+    if wl.block == BLOCK_FFN:
+        return ffn + [("ln_g", (d,), "g"), ("ln_b", (d,), "beta")]
+    if wl.block in (BLOCK_ENC_POSTLN, BLOCK_DEC_PRELN):
+        return ([("wqkv", (3 * d, d), "w"), ("bqkv", (3 * d,), "b"),
+                 ("wo", (d, d), "w"), ("bo", (d,), "b"),
+                 ("ln1_g", (d,), "g"), ("ln1_b", (d,), "beta")]
+                + ffn + [("ln2_g", (d,), "g"), ("ln2_b", (d,), "beta")])
+    if wl.block == BLOCK_ADAPTER:
+        return [("w_down", (f, d), "w"), ("b_down", (f,), "b"),
+                ("w_up", (d, f), "w"), ("b_up", (d,), "b")]
+    raise ValueError(f"unknown block {wl.block}")
+
+
+# ---------------------------------------------------------------- dtype packing
+
+def _round_bf16(a32: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest bf16 (ties to even), returned as fp32 values."""
+    u = np.ascontiguousarray(a32, dtype=np.float32).view(np.uint32)
+    u = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32)
+
+
+def round_to_storage(a32: np.ndarray, dtype: str) -> np.ndarray:
+    """Round fp32 draws to the storage dtype; result is fp32 holding storage-exact values."""
+    if dtype == "bf16":
+        return _round_bf16(a32)
+    if dtype == "f32":
+        return np.ascontiguousarray(a32, dtype=np.float32)
+    raise ValueError(dtype)
+
+
+def to_storage_bytes(a32: np.ndarray, dtype: str) -> np.ndarray:
+    """Storage-exact fp32 values -> the array a device consumer reads (uint16 bf16 bits / fp32)."""
+    a32 = np.ascontiguousarray(a32, dtype=np.float32)
+    if dtype == "bf16":
+        return (a32.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    return a32
+
+
+def storage_to_f64(raw: np.ndarray, dtype: str) -> np.ndarray:
+    """Inverse of to_storage_bytes, widened to fp64 (exact)."""
+    if dtype == "bf16":
+        return (raw.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return raw.astype(np.float64)
+
+
+# ---------------------------------------------------------------- keyed draws
+
+def _gen(seed: int, tag: int, a: int = 0, b: int = 0, c: int = 0) -> np.random.Generator:
+    key0 = (int(seed) << 8) | int(tag)
+    key1 = (int(a) << 24) | (int(b) << 8) | int(c)
+    return np.random.Generator(np.random.Philox(key=[key0, key1]))
+
+
+def tenant_tensors(wl: Workload, tenant: int, layer: int = 0) -> List[np.ndarray]:
+    """All tensors of one (tenant, layer) in canonical order, fp32 arrays holding
+    storage-exact values.  Weights, biases and LayerNorm shifts ~ N(0, 0.02);
+    LayerNorm gains ~ 1 + N(0, 0.02)."""
+    out = []
+    for idx, (_, shape, kind) in enumerate(tensor_specs(wl)):
+        g = _gen(wl.seed, _TAG_WEIGHT, tenant, layer, idx)
+        a = g.standard_normal(int(np.prod(shape)), dtype=np.float32) * np.float32(0.02)
+        if kind == "g":
+            a = a + np.float32(1.0)
+        out.append(round_to_storage(a, wl.dtype).reshape(shape))
+    return out
+
+
+def hidden_states(wl: Workload, request: int, seq_len: int, batch: int = 0) -> np.ndarray:
+    """Hidden states entering the task layers for one request: [seq_len, d] ~ N(0, 1),
+    storage-exact fp32.  Stands in for the PLOT-retrieved representations (Sec. 3.3.1)."""
+    g = _gen(wl.seed, _TAG_X, request, batch & 0xFFFF)
+    a = g.standard_normal(seq_len * wl.d_model, dtype=np.float32)
+    return round_to_storage(a, wl.dtype).reshape(seq_len, wl.d_model)
+
+
+def _popularity_cdf(wl: Workload) -> np.ndarray:
+    k = np.arange(1, wl.n_tenants + 1, dtype=np.float64)
+    p = k ** (-wl.zipf_s) if wl.popularity == "zipf" else np.ones_like(k)
+    c = np.cumsum(p)
+    return c / c[-1]
+
+
+def batch_ids_lens(wl: Workload, batch: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """tenant_ids[R] (i.i.d. uniform or finite Zipf over ranks 1..T, id = rank-1) and
+    seq_lens[R] (fixed, or i.i.d. integer-uniform on [seq_min, seq_max])."""
+    u = _gen(wl.seed, _TAG_IDS, batch).random(wl.n_requests)
+    ids = np.searchsorted(_popularity_cdf(wl), u, side="right")
+    ids = np.minimum(ids, wl.n_tenants - 1).astype(np.int32)
+    if wl.seq_min == wl.seq_max:
+        lens = np.full(wl.n_requests, wl.seq_min, dtype=np.int32)
+    else:
+        lens = _gen(wl.seed, _TAG_LENS, batch).integers(
+            wl.seq_min, wl.seq_max + 1, size=wl.n_requests).astype(np.int32)
+    return ids, lens
