@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Throughput of the mixed-tenant per-tenant-layer forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert_ffn]
+
+One "step" is one pass of the whole hot path (router, residency resolve, grouped GEMMs
+with fused epilogues, attention, LayerNorm) over one seeded synthetic batch that is already
+resident in HBM.  Prints ONE JSON line: tokens/s per layer (whole job), plus
+  roofline     – the dominant kernel (grouped bf16 MFMA GEMM): algorithmic FLOP per launch
+                 / its average launch duration measured with HIP events on the compute
+                 stream, against the 2.5 PFLOP/s dense bf16 peak
+  cpu_baseline – the fp64 oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_F32_TFLOPS = 157.3     # fp32 vector
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by a copy kernel of known size); filled in from profiles/ once measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def linear_flops_per_token(wl) -> float:
+    """2 * (weight elements touched) per token and layer, matrices only."""
+    import synth
+    d, f = wl.d_model, wl.d_ff
+    if wl.block in (synth.BLOCK_FFN, synth.BLOCK_ADAPTER):
+        return 4.0 * d * f
+    return 2.0 * (4 * d * d + 2 * d * f)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="bert_ffn")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="requests the oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; collectives and sharding are not part of it "
+              "(run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth
+    import paper_2504_17449_amd as hmi
+    from paper_2504_17449_amd import harness
+
+    wl = synth.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    ids, lens, x = harness.batch_to_device(wl)
+    N = int(lens.sum())
+    pool = harness.create_pool(wl, max_tokens=N)
+    harness.load_tenants(pool, wl)
+    y = torch.empty_like(x)
+    print(f"[bench] {wl.name}: R={len(ids)} N={N} tenants={wl.n_tenants} distinct={len(set(ids.tolist()))} "
+          f"image={pool.image_bytes / 1e6:.2f} MB setup={time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    def step():
+        pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_layer = ms_per_step / wl.n_layers
+    tokens_per_s = N / (ms_per_layer * 1e-3)
+
+    # ---- dominant kernel: same steps again with HIP events around every kernel launch
+    pool.profile(True)
+    for _ in range(args.steps):
+        step()
+    prof = pool.profile_read()
+    pool.profile(False)
+    gemm = prof["gemm"]
+    gemm_launch_ms = gemm["ms"] / max(gemm["launches"], 1)
+    launches_per_step = gemm["launches"] / args.steps
+    flops_step = linear_flops_per_token(wl) * N * wl.n_layers
+    flops_per_launch = flops_step / launches_per_step
+    bf16 = wl.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+    achieved = flops_per_launch / (gemm_launch_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma" if bf16 else "alu", "kernel": "grouped_gemm", "achieved": round(achieved, 2),
+                "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                "avg_launch_ms": round(gemm_launch_ms, 5), "launches_per_step": launches_per_step,
+                "flop_per_launch": flops_per_launch,
+                "kernel_ms_per_step": {k: round(v["ms"] / args.steps, 5) for k, v in prof.items()}}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same batch
+    cpu = None
+    if args.cpu_sample > 0:
+        from tests.oracle_side import oracle_forward
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        sample = list(range(min(args.cpu_sample, len(ids))))
+        tc = time.perf_counter()
+        oracle_forward(wl, ids, lens, sample)
+        dt = time.perf_counter() - tc
+        toks = int(lens[sample].sum()) * wl.n_layers
+        cpu = {"value": round(toks / dt, 1), "unit": "tokens/s per layer", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {len(sample)} of {len(ids)} requests ({int(lens[sample].sum())} tokens x "
+                         f"{wl.n_layers} layers), numpy fp64, {dt:.1f} s incl. regenerating their weights"}
+
+    stats = pool.stats()
+    pool.close()
+    out = {
+        "metric": "mixed-tenant tokens/sec per layer; grouped-GEMM TFLOP/s as % of bf16 MFMA peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s per layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_tenants} tenants, {len(ids)} requests, {N} tokens, "
+                               f"d={wl.d_model} f={wl.d_ff} heads={wl.n_heads} layers={wl.n_layers}",
+                   "block": wl.block, "tenant_popularity": wl.popularity, "distinct_tenants": len(set(ids.tolist()))},
+        "step_tflops": round(flops_step / (ms_per_step * 1e-3) / 1e12, 2),
+        "step_frac_of_peak": round(flops_step / (ms_per_step * 1e-3) / 1e12 / peak, 4),
+        "pool": stats,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,158 @@
+/*
+ * libhmi — mixed-tenant batched forward of per-tenant transformer layers on one
+ * MI355X (gfx950).
+ *
+ * Problem (HMI, Sec. 6 intro and Sec. 6.3): one inference batch holds requests of many
+ * tenants; every request must be transformed with its own tenant's task-specific
+ * parameters, and doing that tenant by tenant fragments the GPU work.  The paper
+ * stacks the parameters per request and issues one batched matrix multiplication.
+ * This library reaches the same result by ordering the requests by tenant and
+ * running grouped GEMMs whose B operand is looked up, per segment, in a pool of
+ * tenant weight images resident in HBM (optionally backed by pinned host memory
+ * and filled on demand on a side stream, Sec. 5.2 / Sec. 6.2).
+ *
+ * Conventions for every entry point
+ *   - plain C ABI; no exception crosses it; every call returns an int32 status
+ *     (HMI_OK = 0, errors negative).  hmi_last_error() gives a readable reason.
+ *   - "host" / "device" on a pointer says where the memory lives.
+ *   - the library owns: the pool, its HBM slots, pinned host images, workspaces,
+ *     its copy stream and events.  The caller owns x, y, index arrays, weight source
+ *     buffers and the compute stream.
+ *   - not thread-safe per pool; calls on one pool must come from one thread at a time.
+ */
+#ifndef HMI_H
+#define HMI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hmi_pool hmi_pool_t; /* opaque */
+
+enum {
+  HMI_OK = 0,
+  HMI_ERR_ARG = -1,      /* null pointer, bad enum value, inconsistent config          */
+  HMI_ERR_OOM = -2,      /* device or pinned-host allocation failed                    */
+  HMI_ERR_TENANT = -3,   /* tenant id outside [0,max_tenants) or (tenant,layer) never loaded */
+  HMI_ERR_SHAPE = -4,    /* seq_len <= 0, too many requests / tokens, wrong tensor count */
+  HMI_ERR_CAPACITY = -5, /* more distinct tenants needed at once than hbm_slots         */
+  HMI_ERR_DEVICE = -6    /* a HIP runtime call failed                                   */
+};
+
+enum { HMI_F32 = 0, HMI_BF16 = 1 };
+
+/* Per-tenant block kinds.  Matrices are [out,in] row-major: Linear(a) = W a + b (Sec. 3.2.2).
+ * Canonical tensor order of one (tenant, layer):
+ *   FFN         w1[f,d] b1[f] w2[d,f] b2[d] ln_g[d] ln_b[d]
+ *               Y = LN(X + W2 GELU(W1 X + b1) + b2)
+ *   ENC_POSTLN  wqkv[3d,d] bqkv[3d] wo[d,d] bo[d] ln1_g[d] ln1_b[d] w1 b1 w2 b2 ln2_g[d] ln2_b[d]
+ *               X1 = LN1(X + Attn(X));  Y = LN2(X1 + FFN(X1));  bidirectional attention
+ *   DEC_PRELN   same tensors;  X1 = X + Attn(LN1(X));  Y = X1 + FFN(LN2(X1));  causal attention
+ *   ADAPTER     w_down[r,d] b_down[r] w_up[d,r] b_up[d]   (r = d_ff)
+ *               Y = X + Up(ReLU(Down(X)))                 (the paper's adapter, Sec. 3.2.2)
+ * Attention is per request (never across requests), softmax scale 1/sqrt(d/n_heads),
+ * packed qkv in q,k,v order, head h owns columns [h*d_head,(h+1)*d_head).  GELU is the
+ * exact erf form; LayerNorm uses the biased variance and ln_eps inside the square root. */
+enum { HMI_BLOCK_FFN = 0, HMI_BLOCK_ENC_POSTLN = 1, HMI_BLOCK_DEC_PRELN = 2, HMI_BLOCK_ADAPTER = 3 };
+
+typedef struct {
+  int32_t block;        /* HMI_BLOCK_*                                                    */
+  int32_t dtype;        /* HMI_F32 | HMI_BF16: storage type of weights, x and y           */
+  int32_t d_model;      /* multiple of 64 (bf16) / 16 (f32)                               */
+  int32_t d_ff;         /* FFN width, or adapter rank; multiple of 64 (bf16) / 16 (f32)   */
+  int32_t n_heads;      /* attention blocks: d_model / n_heads must be 64; else 0         */
+  int32_t n_layers;     /* per-tenant layers held per tenant (>= 1)                       */
+  int32_t max_tenants;  /* tenant ids live in [0, max_tenants)                            */
+  int32_t hbm_slots;    /* tenants resident in HBM at once (<= max_tenants)               */
+  int32_t host_tier;    /* 1: every loaded tenant also kept in pinned host memory; HBM is
+                           an LRU cache over it, misses are copied in on a side stream    */
+  int32_t max_requests; /* R bound per forward call (<= 2048)                             */
+  int32_t max_tokens;   /* N = sum(seq_lens) bound per forward call                       */
+  float   ln_eps;
+  int32_t device;       /* HIP device ordinal                                             */
+  void*   compute_stream; /* hipStream_t borrowed from the caller; NULL = default stream  */
+} hmi_pool_config_t;
+
+/* Create a pool (Sec. 4.1 "create hPLM" needs somewhere to put instances).  Allocates the
+ * HBM slots (hbm_slots * n_layers images), the workspaces for max_tokens, and, with
+ * host_tier, nothing per tenant yet (pinned images are allocated at load).  *out is set
+ * only on HMI_OK. */
+int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out);
+
+/* Register one (tenant, layer) weight set (Sec. 5.2: a fine-tuned instance's task
+ * parameters are stored once and fetched when requested).  `tensors` is a HOST array of
+ * n_tensors HOST pointers in the canonical order above, each in the pool's dtype, dense
+ * row-major.  The data is copied before return; the caller keeps its buffers.  Without
+ * host_tier the tenant takes an HBM slot for good (HMI_ERR_CAPACITY when none is left);
+ * with host_tier it goes to pinned host memory and into HBM only if a slot is free.
+ * Re-loading a (tenant, layer) replaces its weights. */
+int32_t hmi_pool_load_tenant(hmi_pool_t* pool, int32_t tenant_id, int32_t layer,
+                             const void* const* tensors, int32_t n_tensors);
+
+/* The hot path (Sec. 6.3): y[rows of request r] = block_{tenant_ids[r]}(x[rows of request r]).
+ * x, y: DEVICE, [N, d_model] packed in request order (request r owns rows
+ * tok_off[r] .. tok_off[r]+seq_lens[r]), pool dtype, x != y, x is not modified.
+ * tenant_ids, seq_lens: HOST int32[n_requests]; copied before return.
+ * Work is enqueued on compute_stream and the call returns without waiting for it.
+ * Errors are detected before anything is enqueued, so y is untouched on error:
+ * unknown / unloaded tenant -> HMI_ERR_TENANT; seq_len <= 0, R or N over the configured
+ * bound -> HMI_ERR_SHAPE; more distinct tenants than hbm_slots -> HMI_ERR_CAPACITY.
+ * n_requests == 0 is HMI_OK and does nothing. */
+int32_t hmi_layer_forward(hmi_pool_t* pool, int32_t layer, const void* x, void* y,
+                          const int32_t* tenant_ids, const int32_t* seq_lens,
+                          int32_t n_requests);
+
+/* Several consecutive layers [layer_begin, layer_end) of every request's tenant in one call
+ * (the paper's hPLM runs a stack of task-adapted higher layers per request, Sec. 3.3.2, and
+ * prefetches layer l+1's task parameters while layer l computes, Sec. 6.2).  Same arguments,
+ * errors and asynchrony as hmi_layer_forward.  The batch is routed once; between layers the
+ * activations stay in fp32 inside the library and only the last layer rounds into y; with
+ * host_tier the swap-in of layer l+1 is enqueued on the copy stream before layer l's
+ * kernels.  hmi_layer_forward(layer) is hmi_stack_forward(layer, layer+1). */
+int32_t hmi_stack_forward(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_end,
+                          const void* x, void* y, const int32_t* tenant_ids,
+                          const int32_t* seq_lens, int32_t n_requests);
+
+/* Routing of the last forward call, for bit-exact checks of the tenant-segmented router:
+ * perm[R] (stable order of requests by tenant id), seg_tenant[G], seg_req_off[G+1],
+ * seg_tok_off[G+1] (segment bounds in sorted requests / sorted tokens), *n_segments = G.
+ * All HOST buffers sized for max_requests(+1); any may be NULL.  Waits for the router. */
+int32_t hmi_get_route(hmi_pool_t* pool, int32_t* perm, int32_t* seg_tenant,
+                      int32_t* seg_req_off, int32_t* seg_tok_off, int32_t* n_segments);
+
+/* Pipelined swapping (Sec. 6.2): start bringing `layer` of these tenants into HBM on the
+ * library's copy stream while the compute stream is busy with an earlier batch or layer.
+ * HOST int32[n].  Tenants already resident are only marked recently used.  No-op without
+ * host_tier.  Best effort: stops silently when no evictable slot is left. */
+int32_t hmi_pool_prefetch(hmi_pool_t* pool, int32_t layer, const int32_t* tenant_ids, int32_t n);
+
+/* Counters since creation: hits / misses count distinct (tenant, layer) lookups made by
+ * forward calls; bytes_h2d counts swap-in traffic.  Any pointer may be NULL. */
+int32_t hmi_pool_stats(hmi_pool_t* pool, int64_t* hits, int64_t* misses, int64_t* bytes_h2d,
+                       int64_t* evictions);
+
+/* Per-kernel timing for measurement: while enabled, every kernel the forward calls launch
+ * is bracketed by HIP events on compute_stream.  hmi_pool_profile_read waits for the
+ * stream, then writes the summed milliseconds and the launch count of each kernel kind
+ * (HOST arrays of HMI_KERNEL_KINDS entries, either may be NULL) and clears the record. */
+enum { HMI_KERNEL_ROUTER = 0, HMI_KERNEL_GEMM = 1, HMI_KERNEL_ATTENTION = 2,
+       HMI_KERNEL_LAYERNORM = 3, HMI_KERNEL_KINDS = 4 };
+int32_t hmi_pool_profile(hmi_pool_t* pool, int32_t enable);
+int32_t hmi_pool_profile_read(hmi_pool_t* pool, double* ms, int64_t* launches);
+
+/* Bytes of one (tenant, layer) image in HBM (tensors padded to 256 B). */
+int64_t hmi_pool_image_bytes(const hmi_pool_t* pool);
+
+/* Static string describing the last error on this pool (or the last create error when
+ * pool is NULL).  Valid until the next call on the pool. */
+const char* hmi_last_error(const hmi_pool_t* pool);
+
+/* Waits for both streams, frees everything the library owns.  NULL is fine. */
+int32_t hmi_pool_destroy(hmi_pool_t* pool);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HMI_H */

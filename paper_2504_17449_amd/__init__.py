@@ -1,0 +1,239 @@
+"""Python binding over libhmi.so (argument marshalling only).
+
+Every step of the mixed-tenant layer forward runs inside the HIP library; this module
+turns torch tensors / numpy arrays into raw pointers and forwards the call under the
+same names as the C ABI (include/hmi.h).  There is no CPU fallback: importing the
+binding without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhmi.so")
+
+HMI_OK, HMI_ERR_ARG, HMI_ERR_OOM, HMI_ERR_TENANT, HMI_ERR_SHAPE, HMI_ERR_CAPACITY, HMI_ERR_DEVICE = \
+    0, -1, -2, -3, -4, -5, -6
+HMI_F32, HMI_BF16 = 0, 1
+HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER = 0, 1, 2, 3
+
+EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_layer_forward", "hmi_stack_forward",
+           "hmi_get_route",
+           "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
+           "hmi_pool_destroy"]
+
+
+class hmi_pool_config_t(C.Structure):
+    _fields_ = [("block", C.c_int32), ("dtype", C.c_int32), ("d_model", C.c_int32),
+                ("d_ff", C.c_int32), ("n_heads", C.c_int32), ("n_layers", C.c_int32),
+                ("max_tenants", C.c_int32), ("hbm_slots", C.c_int32), ("host_tier", C.c_int32),
+                ("max_requests", C.c_int32), ("max_tokens", C.c_int32), ("ln_eps", C.c_float),
+                ("device", C.c_int32), ("compute_stream", C.c_void_p)]
+
+
+class HmiError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libhmi error {code}: {msg}")
+        self.code = code
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python paper_2504_17449_amd/build.py` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
+    pi32 = C.POINTER(C.c_int32)
+    lib.hmi_pool_create.argtypes = [C.POINTER(hmi_pool_config_t), C.POINTER(vp)]
+    lib.hmi_pool_create.restype = i32
+    lib.hmi_pool_load_tenant.argtypes = [vp, i32, i32, C.POINTER(vp), i32]
+    lib.hmi_pool_load_tenant.restype = i32
+    lib.hmi_layer_forward.argtypes = [vp, i32, vp, vp, pi32, pi32, i32]
+    lib.hmi_layer_forward.restype = i32
+    lib.hmi_stack_forward.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
+    lib.hmi_stack_forward.restype = i32
+    lib.hmi_get_route.argtypes = [vp, pi32, pi32, pi32, pi32, pi32]
+    lib.hmi_get_route.restype = i32
+    lib.hmi_pool_prefetch.argtypes = [vp, i32, pi32, i32]
+    lib.hmi_pool_prefetch.restype = i32
+    lib.hmi_pool_stats.argtypes = [vp] + [C.POINTER(i64)] * 4
+    lib.hmi_pool_stats.restype = i32
+    lib.hmi_pool_profile.argtypes = [vp, i32]
+    lib.hmi_pool_profile.restype = i32
+    lib.hmi_pool_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.hmi_pool_profile_read.restype = i32
+    lib.hmi_pool_image_bytes.argtypes = [vp]
+    lib.hmi_pool_image_bytes.restype = i64
+    lib.hmi_last_error.argtypes = [vp]
+    lib.hmi_last_error.restype = C.c_char_p
+    lib.hmi_pool_destroy.argtypes = [vp]
+    lib.hmi_pool_destroy.restype = i32
+    return lib
+
+
+lib = _load()
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def _p32(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+# ---------------------------------------------------------------- same names as the C ABI
+
+def hmi_last_error(pool: Optional[int]) -> str:
+    return (lib.hmi_last_error(pool) or b"").decode()
+
+
+def hmi_pool_create(*, block: int, dtype: int, d_model: int, d_ff: int, n_heads: int = 0,
+                    n_layers: int = 1, max_tenants: int, hbm_slots: Optional[int] = None,
+                    host_tier: bool = False, max_requests: int, max_tokens: int,
+                    ln_eps: float = 1e-12, device: int = 0, compute_stream: int = 0):
+    """-> (status, pool handle or None).  compute_stream: raw hipStream_t (torch's
+    ``torch.cuda.current_stream().cuda_stream``), 0 = default stream."""
+    cfg = hmi_pool_config_t(block, dtype, d_model, d_ff, n_heads, n_layers, max_tenants,
+                            max_tenants if hbm_slots is None else hbm_slots, int(host_tier),
+                            max_requests, max_tokens, ln_eps, device, compute_stream or None)
+    out = C.c_void_p()
+    rc = lib.hmi_pool_create(C.byref(cfg), C.byref(out))
+    return rc, (out.value if rc == HMI_OK else None)
+
+
+def hmi_pool_load_tenant(pool: int, tenant_id: int, layer: int, tensors: Sequence[np.ndarray]) -> int:
+    """tensors: host numpy arrays in canonical order, already in the pool's storage dtype
+    (uint16 bf16 bit patterns or float32), C-contiguous."""
+    keep = [np.ascontiguousarray(t) for t in tensors]
+    arr = (C.c_void_p * len(keep))(*[t.ctypes.data for t in keep])
+    return lib.hmi_pool_load_tenant(pool, tenant_id, layer, arr, len(keep))
+
+
+def hmi_layer_forward(pool: int, layer: int, x_ptr: int, y_ptr: int, tenant_ids, seq_lens) -> int:
+    """x_ptr / y_ptr: device addresses (tensor.data_ptr()); tenant_ids / seq_lens: host ints."""
+    ids, lens = _i32(tenant_ids), _i32(seq_lens)
+    if ids.shape != lens.shape or ids.ndim != 1:
+        raise ValueError("tenant_ids and seq_lens must be 1-D and of equal length")
+    return lib.hmi_layer_forward(pool, layer, x_ptr, y_ptr, _p32(ids), _p32(lens), ids.shape[0])
+
+
+def hmi_stack_forward(pool: int, layer_begin: int, layer_end: int, x_ptr: int, y_ptr: int,
+                      tenant_ids, seq_lens) -> int:
+    ids, lens = _i32(tenant_ids), _i32(seq_lens)
+    if ids.shape != lens.shape or ids.ndim != 1:
+        raise ValueError("tenant_ids and seq_lens must be 1-D and of equal length")
+    return lib.hmi_stack_forward(pool, layer_begin, layer_end, x_ptr, y_ptr, _p32(ids), _p32(lens),
+                                 ids.shape[0])
+
+
+def hmi_get_route(pool: int, max_requests: int):
+    perm = np.zeros(max_requests, np.int32)
+    seg_tenant = np.zeros(max_requests, np.int32)
+    seg_req_off = np.zeros(max_requests + 1, np.int32)
+    seg_tok_off = np.zeros(max_requests + 1, np.int32)
+    G = C.c_int32(0)
+    rc = lib.hmi_get_route(pool, _p32(perm), _p32(seg_tenant), _p32(seg_req_off), _p32(seg_tok_off),
+                           C.byref(G))
+    g = G.value
+    return rc, {"perm": perm, "seg_tenant": seg_tenant[:g], "seg_req_off": seg_req_off[:g + 1],
+                "seg_tok_off": seg_tok_off[:g + 1], "n_segments": g}
+
+
+def hmi_pool_prefetch(pool: int, layer: int, tenant_ids) -> int:
+    ids = _i32(tenant_ids)
+    return lib.hmi_pool_prefetch(pool, layer, _p32(ids), ids.shape[0])
+
+
+def hmi_pool_stats(pool: int) -> dict:
+    v = [C.c_int64(0) for _ in range(4)]
+    lib.hmi_pool_stats(pool, *[C.byref(x) for x in v])
+    return dict(zip(("hits", "misses", "bytes_h2d", "evictions"), (x.value for x in v)))
+
+
+KERNEL_KINDS = ("router", "gemm", "attention", "layernorm")
+
+
+def hmi_pool_profile(pool: int, enable: bool) -> int:
+    return lib.hmi_pool_profile(pool, int(enable))
+
+
+def hmi_pool_profile_read(pool: int):
+    ms = (C.c_double * len(KERNEL_KINDS))()
+    n = (C.c_int64 * len(KERNEL_KINDS))()
+    rc = lib.hmi_pool_profile_read(pool, ms, n)
+    return rc, {k: {"ms": ms[i], "launches": n[i]} for i, k in enumerate(KERNEL_KINDS)}
+
+
+def hmi_pool_image_bytes(pool: int) -> int:
+    return lib.hmi_pool_image_bytes(pool)
+
+
+def hmi_pool_destroy(pool: Optional[int]) -> int:
+    return lib.hmi_pool_destroy(pool)
+
+
+# ---------------------------------------------------------------- convenience wrapper
+
+class Pool:
+    """Owns one hmi pool handle; raises HmiError on any non-zero status."""
+
+    def __init__(self, **cfg):
+        self.max_requests = cfg["max_requests"]
+        rc, h = hmi_pool_create(**cfg)
+        if rc != HMI_OK:
+            raise HmiError(rc, hmi_last_error(None))
+        self.h = h
+
+    def _check(self, rc: int) -> None:
+        if rc != HMI_OK:
+            raise HmiError(rc, hmi_last_error(self.h))
+
+    def load_tenant(self, tenant_id: int, layer: int, tensors) -> None:
+        self._check(hmi_pool_load_tenant(self.h, tenant_id, layer, tensors))
+
+    def forward(self, layer: int, x, y, tenant_ids, seq_lens) -> None:
+        """x, y: torch tensors on the pool's device ([N, d], pool dtype, contiguous)."""
+        self._check(hmi_layer_forward(self.h, layer, x.data_ptr(), y.data_ptr(), tenant_ids, seq_lens))
+
+    def stack_forward(self, layer_begin: int, layer_end: int, x, y, tenant_ids, seq_lens) -> None:
+        self._check(hmi_stack_forward(self.h, layer_begin, layer_end, x.data_ptr(), y.data_ptr(),
+                                      tenant_ids, seq_lens))
+
+    def route(self) -> dict:
+        rc, rt = hmi_get_route(self.h, self.max_requests)
+        self._check(rc)
+        return rt
+
+    def prefetch(self, layer: int, tenant_ids) -> None:
+        self._check(hmi_pool_prefetch(self.h, layer, tenant_ids))
+
+    def profile(self, enable: bool) -> None:
+        self._check(hmi_pool_profile(self.h, enable))
+
+    def profile_read(self) -> dict:
+        rc, out = hmi_pool_profile_read(self.h)
+        self._check(rc)
+        return out
+
+    def stats(self) -> dict:
+        return hmi_pool_stats(self.h)
+
+    @property
+    def image_bytes(self) -> int:
+        return hmi_pool_image_bytes(self.h)
+
+    def close(self) -> None:
+        if self.h is not None:
+            hmi_pool_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,221 @@
+// Grouped bf16 GEMM on the gfx950 matrix cores with fused epilogues.
+//
+// Computes, for every m-tile the router emitted (all rows of a tile belong to one tenant
+// segment g):   C[rows, :] = epi( A[rows, :] * W_g^T + b_g )
+// where W_g ([n_out, k] row-major, i.e. Linear(a) = W a + b of Sec. 3.2.2) is read from
+// the HBM slot of segment g.  This is the "different requests, different parameters, one
+// launch" step of Sec. 6.3 without materialising per-request parameter copies.
+//
+// Mapping to the hardware
+//   * v_mfma_f32_32x32x16_bf16: both operands are K-contiguous, which is exactly how the
+//     activations ([row, k]) and the weights ([out, k]) are stored, so an operand fragment
+//     is one 16-byte LDS read per lane.
+//   * workgroup tile BM x BN x 64 staged through double-buffered LDS; 16-byte chunks are
+//     XOR-swizzled by row so that the 32 rows a half-wavefront reads hit distinct banks.
+//   * wavefronts are laid out WM x WN; each owns (BM/WM) x (BN/WN) of C in accumulators.
+//   * workgroup ids are folded so that each of the 8 XCDs (which get workgroups round
+//     robin) works on a contiguous range of tiles: tiles that share a weight panel or an
+//     activation panel then share that XCD's L2.
+#include "hmi_kernels.h"
+
+namespace hmi {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;          // k extent of one LDS stage (8 chunks of 8 bf16)
+constexpr int kXcds = 8;
+
+__device__ __forceinline__ float bf2f(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  __bf16 b = (__bf16)f;  // round to nearest even
+  return __builtin_bit_cast(uint16_t, b);
+}
+__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g, Route rt) {
+  constexpr int NTH = 64 * WM * WN;
+  constexpr int WTM = BM / WM, WTN = BN / WN;      // wavefront tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wavefront
+  constexpr int A_IT = BM * 8 / NTH, B_IT = BN * 8 / NTH;
+  static_assert(BM * 8 % NTH == 0 && BN * 8 % NTH == 0, "tile/threads mismatch");
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* As = reinterpret_cast<uint16_t*>(smem);                 // [2][BM*BK]
+  uint16_t* Bs = As + 2 * BM * BK;                                  // [2][BN*BK]
+  int* rowsrc_s = reinterpret_cast<int*>(Bs + 2 * BN * BK);         // [BM]
+
+  // ---- which tile
+  const int nt_n = (g.n_out + BN - 1) / BN;
+  const int total = g.n_mtiles * nt_n;
+  const int per = (total + kXcds - 1) / kXcds;
+  const int local = blockIdx.x / kXcds;
+  const int w = (blockIdx.x % kXcds) * per + local;
+  if (local >= per || w >= total) return;
+  const int mt = w / nt_n, n0 = (w % nt_n) * BN;
+  const int seg = rt.tile_seg[g.which_tiles][mt];
+  const int row0 = rt.tile_row0[g.which_tiles][mt];
+  const int rows = min(BM, rt.seg_tok_off[seg + 1] - row0);
+  const size_t slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(g.pool + slot_base + g.w_off);
+  const uint16_t* bias = reinterpret_cast<const uint16_t*>(g.pool + slot_base + g.b_off);
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(g.A);
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int wm = wave / WN, wn = wave % WN;
+  const int K = g.k;
+
+  for (int i = t; i < BM; i += NTH) rowsrc_s[i] = rt.row_src[row0 + min(i, rows - 1)];
+  __syncthreads();
+
+  // ---- per-thread global source pointers and LDS destinations of the staging copies
+  const uint16_t* a_src[A_IT];
+  const uint16_t* b_src[B_IT];
+  int a_dst[A_IT], b_dst[B_IT];
+#pragma unroll
+  for (int i = 0; i < A_IT; ++i) {
+    const int q = t + NTH * i, row = q >> 3, c = q & 7;
+    a_src[i] = A + (size_t)rowsrc_s[row] * g.lda + c * 8;
+    a_dst[i] = row * BK + ((c ^ swz(row)) << 3);
+  }
+#pragma unroll
+  for (int i = 0; i < B_IT; ++i) {
+    const int q = t + NTH * i, row = q >> 3, c = q & 7;
+    b_src[i] = W + (size_t)min(n0 + row, g.n_out - 1) * K + c * 8;
+    b_dst[i] = row * BK + ((c ^ swz(row)) << 3);
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // A wavefront whose rows all lie beyond the tile's row count has nothing to multiply.
+  const bool wave_active = wm * WTM < rows;
+
+  uint4 ra[A_IT], rb[B_IT];
+#pragma unroll
+  for (int i = 0; i < A_IT; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_src[i]);
+#pragma unroll
+  for (int i = 0; i < B_IT; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i]);
+#pragma unroll
+  for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4*>(As + a_dst[i]) = ra[i];
+#pragma unroll
+  for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4*>(Bs + b_dst[i]) = rb[i];
+  __syncthreads();
+
+  const int KT = K / BK;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int cur = kt & 1;
+    const bool more = kt + 1 < KT;
+    if (more) {
+      const int k1 = (kt + 1) * BK;
+#pragma unroll
+      for (int i = 0; i < A_IT; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_src[i] + k1);
+#pragma unroll
+      for (int i = 0; i < B_IT; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + k1);
+    }
+    if (wave_active) {
+      const uint16_t* Ac = As + cur * BM * BK;
+      const uint16_t* Bc = Bs + cur * BN * BK;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        const int chunk = ks * 2 + lh;
+        bf16x8 fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int row = wm * WTM + i * 32 + l32;
+          fa[i] = *reinterpret_cast<const bf16x8*>(Ac + row * BK + ((chunk ^ swz(row)) << 3));
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int row = wn * WTN + j * 32 + l32;
+          fb[j] = *reinterpret_cast<const bf16x8*>(Bc + row * BK + ((chunk ^ swz(row)) << 3));
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    if (more) {
+      uint16_t* An = As + (cur ^ 1) * BM * BK;
+      uint16_t* Bn = Bs + (cur ^ 1) * BN * BK;
+#pragma unroll
+      for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4*>(An + a_dst[i]) = ra[i];
+#pragma unroll
+      for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4*>(Bn + b_dst[i]) = rb[i];
+    }
+    __syncthreads();
+  }
+
+  if (!wave_active) return;
+
+  // ---- epilogue.  Accumulator register r of tile (i,j) holds
+  //      row = 8*(r/4) + 4*(lane/32) + r%4,  column = lane%32.
+  const int epi = g.epi;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn * WTN + j * 32 + l32;
+    if (col >= g.n_out) continue;
+    const float bv = bf2f(bias[col]);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = wm * WTM + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+        if (m >= rows) continue;
+        const size_t orow = (size_t)rowsrc_s[m];
+        float v = acc[i][j][r] + bv;
+        if (epi == EPI_BIAS_GELU) v = gelu_erf(v);
+        else if (epi == EPI_BIAS_RELU) v = fmaxf(v, 0.0f);
+        else if (epi == EPI_BIAS_RESID) {
+          v += g.resid_f32 ? reinterpret_cast<const float*>(g.resid)[orow * g.ldr + col]
+                           : bf2f(reinterpret_cast<const uint16_t*>(g.resid)[orow * g.ldr + col]);
+        }
+        if (g.out_f32) reinterpret_cast<float*>(g.C)[orow * g.ldc + col] = v;
+        else reinterpret_cast<uint16_t*>(g.C)[orow * g.ldc + col] = f2bf(v);
+        if (g.C2) reinterpret_cast<uint16_t*>(g.C2)[orow * g.ldc + col] = f2bf(v);
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN>
+void launch_cfg(const GemmArgs& g, const Route& rt, hipStream_t s) {
+  constexpr int NTH = 64 * WM * WN;
+  const size_t lds = (size_t)2 * (BM + BN) * BK * 2 + BM * sizeof(int);
+  static bool attr_set = false;
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN>;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_set = true;
+  }
+  const int nt_n = (g.n_out + BN - 1) / BN;
+  const long long total = (long long)g.n_mtiles * nt_n;
+  if (total <= 0) return;
+  const int per = (int)((total + kXcds - 1) / kXcds);
+  hipLaunchKernelGGL(kern, dim3(per * kXcds), dim3(NTH), lds, s, g, rt);
+}
+
+}  // namespace
+
+int gemm_bf16_tile_m(int, int) { return 256; }
+
+void launch_gemm_bf16(const GemmArgs& g, const Route& rt, hipStream_t s) {
+  if (g.n_out % 256 == 0) launch_cfg<256, 256, 4, 2>(g, rt, s);
+  else if (g.n_out % 128 == 0) launch_cfg<256, 128, 4, 2>(g, rt, s);
+  else launch_cfg<256, 64, 8, 1>(g, rt, s);
+}
+
+}  // namespace hmi

@@ -1,0 +1,82 @@
+// Internal launch interface between the pool/orchestration code and the gfx950 kernels.
+// Everything here is device-pointer plumbing; the C ABI lives in include/hmi.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hmi {
+
+constexpr int kRouterThreads = 1024;
+constexpr int kMaxRequests = 2048;   // router keeps keys/values of one batch in LDS
+
+// Output of the tenant-segmented router, all DEVICE int32 arrays.
+struct Route {
+  const int32_t* tenant_ids;  // [R] in: request -> tenant
+  const int32_t* seq_lens;    // [R] in
+  const int32_t* req_slot;    // [R] in: request -> HBM slot of its tenant (resolved on host)
+  int32_t* perm;              // [R]   sorted position -> request
+  int32_t* tok_off;           // [R+1] request -> first row (original packed order)
+  int32_t* seg_tenant;        // [G]
+  int32_t* seg_slot;          // [G]
+  int32_t* seg_req_off;       // [G+1] segment -> first sorted position
+  int32_t* seg_tok_off;       // [G+1] segment -> first sorted row
+  int32_t* row_src;           // [N]   sorted row -> original row
+  int32_t* n_segments;        // [1]
+  // m-tile work lists for two tile heights (rows of one tile never cross a segment)
+  int32_t* tile_seg[2];       // [tiles] tile -> segment
+  int32_t* tile_row0[2];      // [tiles] tile -> first sorted row
+  int32_t* n_tiles[2];        // [1]
+  int32_t tile_m[2];          // tile heights (0 = list unused)
+  int32_t key_bits;           // bits needed for the largest tenant id (radix passes = bits/4)
+};
+
+void launch_router(const Route& rt, int R, hipStream_t s);
+
+enum Epilogue : int {
+  EPI_BIAS = 0,        // C = acc + b                      -> storage dtype
+  EPI_BIAS_GELU = 1,   // C = GELU(acc + b)                -> storage dtype
+  EPI_BIAS_RELU = 2,   // C = max(acc + b, 0)              -> storage dtype
+  EPI_BIAS_RESID = 3   // C = acc + b + resid              -> out_f32 ? fp32 : storage dtype
+};
+
+// Grouped GEMM: for every m-tile (segment g, rows), C[rows, :] = epi(A[rows, :] * W_g^T + b_g)
+// with W_g = slot image of seg_slot[g] (+w_off), [n_out, k] row-major.  Rows are addressed
+// through row_src (original packed order) in A, C and resid alike.
+struct GemmArgs {
+  const void* A;  int lda;            // storage dtype, [N, k]
+  void* C;        int ldc;            // [N, n_out]
+  void* C2;                           // optional second copy of C in the storage dtype (same ldc)
+  const void* resid; int ldr;         // EPI_BIAS_RESID only
+  int resid_f32;                      // residual operand is fp32 (else storage dtype)
+  int out_f32;                        // write fp32 (else storage dtype)
+  const char* pool; size_t slot_stride;  // HBM pool base and bytes per slot
+  size_t w_off, b_off;                // byte offsets of W and bias inside a slot (layer included)
+  int n_out, k;
+  int epi;
+  int which_tiles;                    // index into Route::tile_* (tile height)
+  int n_mtiles;                       // exact count, computed on the host
+};
+
+void launch_gemm_bf16(const GemmArgs& g, const Route& rt, hipStream_t s);
+void launch_gemm_f32(const GemmArgs& g, const Route& rt, hipStream_t s);
+int  gemm_bf16_tile_m(int n_out, int k);  // tile height the bf16 kernel will use for this shape
+
+// Row LayerNorm with per-tenant gain/shift looked up through the route.
+// in: fp32 (in_f32) or storage dtype; writes out_f32 (fp32, may be null) and/or
+// out_st (storage dtype, may be null).  All [N, d] in original packed order.
+struct LnArgs {
+  const void* in; int in_f32;
+  float* out_f32; void* out_st;
+  const char* pool; size_t slot_stride; size_t g_off, b_off;
+  int d; float eps; int n_rows; int bf16;
+};
+void launch_layernorm(const LnArgs& a, const Route& rt, hipStream_t s);
+
+// Per-request multi-head attention on packed qkv [N, 3d] (q | k | v) -> ctx [N, d].
+struct AttnArgs {
+  const void* qkv; void* ctx; int d; int n_heads; int causal; int R; int max_len; int bf16;
+  int n_rows;  // N = total rows (fp32 kernel: one wavefront per row and head)
+};
+void launch_attention(const AttnArgs& a, const Route& rt, hipStream_t s);
+
+}  // namespace hmi

@@ -1,0 +1,88 @@
+// Row LayerNorm with per-tenant gain and shift: y = (x - mean) / sqrt(var + eps) * g_t + b_t,
+// biased variance, statistics in fp32.  One wavefront per row; the row's tenant slot is
+// found by a binary search of the row's sorted position in the segment token offsets.
+// Used after the residual adds of the per-tenant blocks (post-LN) or before the
+// sub-layers (pre-LN); the paper leaves these to BERT / GPT's layer definitions.
+#include "hmi_kernels.h"
+
+namespace hmi {
+namespace {
+
+__device__ __forceinline__ float bf2f(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+constexpr int kMaxPerLane = 32;  // d <= 2048
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a, Route rt) {
+  const int lane = threadIdx.x & 63;
+  const int srow = blockIdx.x * 4 + (threadIdx.x >> 6);  // sorted row
+  if (srow >= a.n_rows) return;
+  // segment of this sorted row: last g with seg_tok_off[g] <= srow
+  int lo = 0, hi = rt.n_segments[0];
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (rt.seg_tok_off[mid] <= srow) lo = mid; else hi = mid;
+  }
+  const size_t slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
+  const size_t row = (size_t)rt.row_src[srow];
+  const int d = a.d, per = d >> 6;
+
+  float v[kMaxPerLane];
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i) {
+    if (i < per) {
+      const size_t idx = row * d + lane + 64 * i;
+      if (a.in_f32) v[i] = reinterpret_cast<const float*>(a.in)[idx];
+      else v[i] = BF16 ? bf2f(reinterpret_cast<const uint16_t*>(a.in)[idx])
+                       : reinterpret_cast<const float*>(a.in)[idx];
+      s += v[i];
+    }
+  }
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.0f;
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i)
+    if (i < per) { const float c = v[i] - mean; q += c * c; }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + a.eps);
+
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i) {
+    if (i < per) {
+      const int col = lane + 64 * i;
+      float gg, bb;
+      if (BF16) {
+        gg = bf2f(reinterpret_cast<const uint16_t*>(a.pool + slot_base + a.g_off)[col]);
+        bb = bf2f(reinterpret_cast<const uint16_t*>(a.pool + slot_base + a.b_off)[col]);
+      } else {
+        gg = reinterpret_cast<const float*>(a.pool + slot_base + a.g_off)[col];
+        bb = reinterpret_cast<const float*>(a.pool + slot_base + a.b_off)[col];
+      }
+      const float y = (v[i] - mean) * rstd * gg + bb;
+      const size_t idx = row * d + col;
+      if (a.out_f32) a.out_f32[idx] = y;
+      if (a.out_st) {
+        if (BF16) reinterpret_cast<uint16_t*>(a.out_st)[idx] = f2bf(y);
+        else reinterpret_cast<float*>(a.out_st)[idx] = y;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+void launch_layernorm(const LnArgs& a, const Route& rt, hipStream_t s) {
+  if (a.n_rows <= 0) return;
+  const unsigned blocks = (unsigned)((a.n_rows + 3) / 4);
+  if (a.bf16) hipLaunchKernelGGL(layernorm_kernel<true>, dim3(blocks), dim3(256), 0, s, a, rt);
+  else hipLaunchKernelGGL(layernorm_kernel<false>, dim3(blocks), dim3(256), 0, s, a, rt);
+}
+
+}  // namespace hmi

@@ -1,0 +1,752 @@
+// libhmi host side: the tenant pool (HBM slots, optional pinned-host tier with LRU
+// swap-in on a side stream) and the per-block kernel sequence behind hmi_layer_forward.
+// See include/hmi.h for the contract of every entry point.
+//
+// Paper passages realised here: instances are created once and their task parameters
+// kept in host memory, fetched to the GPU when requested (Sec. 5.2); loading and compute
+// run on different streams so that they overlap, per batch and per layer (Sec. 6.2);
+// one batch mixes tenants and is executed in one set of launches (Sec. 6.3).
+#include "../../include/hmi.h"
+#include "hmi_kernels.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace hmi;
+
+namespace {
+
+constexpr int kRing = 8;
+constexpr size_t kAlign = 256;
+constexpr int kArenaImages = 32;  // pinned host images per hipHostMalloc call
+
+char g_create_error[256] = "";
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Events for work enqueued in order on one stream, addressed by a growing sequence
+// number.  Waiting for sequence s means waiting for the newest recorded event whose
+// sequence is >= s and still in the ring (a later event on the same stream implies s).
+struct EventRing {
+  hipEvent_t ev[kRing] = {};
+  uint64_t next = 1;  // sequence the next record() will get
+  bool init() {
+    for (auto& e : ev)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return false;
+    return true;
+  }
+  void destroy() {
+    for (auto& e : ev)
+      if (e) (void)hipEventDestroy(e);
+  }
+  uint64_t record(hipStream_t s) {
+    (void)hipEventRecord(ev[next % kRing], s);
+    return next++;
+  }
+  hipEvent_t at_least(uint64_t seq) const {
+    uint64_t newest = next - 1;
+    uint64_t oldest = newest >= (uint64_t)kRing ? newest - kRing + 1 : 1;
+    return ev[std::max(seq, oldest) % kRing];
+  }
+};
+
+struct TensorLoc { size_t off, bytes; };
+
+}  // namespace
+
+struct hmi_pool {
+  hmi_pool_config_t cfg{};
+  int esize = 2;
+  bool bf16 = true;
+  std::vector<TensorLoc> tl;   // inside one (tenant, layer) image
+  size_t image_bytes = 0;      // one layer
+  size_t slot_stride = 0;      // all layers of a tenant
+  char* d_pool = nullptr;
+
+  // residency
+  std::vector<int32_t> slot_of_tenant, tenant_of_slot;
+  std::vector<uint8_t> loaded;       // [tenant*L + layer] weights registered
+  std::vector<uint8_t> slot_valid;   // [slot*L + layer] HBM copy present (or in flight)
+  std::vector<uint64_t> slot_stamp;  // LRU clock of last use
+  std::vector<uint64_t> slot_fwd;    // forward sequence that last read the slot
+  std::vector<uint64_t> slot_copy;   // copy sequence that last wrote the slot
+  std::vector<int32_t> free_slots;
+  uint64_t clock = 0;
+  std::vector<char*> host_img;       // [tenant] pinned, all layers (host tier)
+  std::vector<char*> arenas;
+  char* arena_cur = nullptr;
+  int arena_left = 0;
+
+  // streams and ordering
+  hipStream_t compute = nullptr, copy = nullptr;
+  EventRing fwd_done, copy_done;
+  uint64_t copy_waited_fwd = 0;     // copy stream has waited for forwards up to here
+  uint64_t compute_waited_copy = 0; // compute stream has waited for copies up to here
+
+  // staging for load_tenant without host tier
+  char* stage[2] = {nullptr, nullptr};
+  hipEvent_t stage_ev[2] = {};
+  int stage_i = 0;
+
+  // per-call index staging (pinned) and device index arrays
+  int32_t* h_idx[4] = {};
+  hipEvent_t idx_ev[4] = {};
+  int idx_i = 0;
+  int32_t* d_idx = nullptr;   // all device int32 routing arrays, one allocation
+  Route rt{};
+  int last_R = 0;
+  int tile_m = 256;
+
+  // workspaces
+  char *w_qkv = nullptr, *w_ctx = nullptr, *w_hmid = nullptr, *w_act = nullptr;
+  float *w_z = nullptr, *w_x1 = nullptr, *w_y32 = nullptr;
+  char* w_yst = nullptr;       // inter-layer activations of a multi-layer call
+
+  // host scratch
+  std::vector<uint32_t> mark;       // [tenant] epoch when last seen in a batch
+  std::vector<int32_t> tok_count;   // [tenant]
+  std::vector<int32_t> distinct;
+  uint32_t epoch = 0;
+
+  int64_t hits = 0, misses = 0, bytes_h2d = 0, evictions = 0;
+
+  // optional per-kernel timing (hipEvents around each launch on the compute stream)
+  bool profiling = false;
+  struct Span { int kind; hipEvent_t a, b; };
+  std::vector<Span> spans;
+  char err[256] = "";
+};
+
+namespace {
+
+int32_t fail(hmi_pool* p, int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(p ? p->err : g_create_error, 256, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(p, call)                                                              \
+  do {                                                                                \
+    hipError_t e_ = (call);                                                           \
+    if (e_ != hipSuccess)                                                             \
+      return fail(p, e_ == hipErrorOutOfMemory ? HMI_ERR_OOM : HMI_ERR_DEVICE,        \
+                  "%s failed: %s", #call, hipGetErrorString(e_));                     \
+  } while (0)
+
+// Canonical tensor shapes (rows, cols) per block; cols == 0 for vectors.
+std::vector<std::pair<int64_t, int64_t>> tensor_shapes(const hmi_pool_config_t& c) {
+  const int64_t d = c.d_model, f = c.d_ff;
+  std::vector<std::pair<int64_t, int64_t>> ffn = {{f, d}, {f, 0}, {d, f}, {d, 0}};
+  std::vector<std::pair<int64_t, int64_t>> out;
+  switch (c.block) {
+    case HMI_BLOCK_FFN:
+      out = ffn; out.push_back({d, 0}); out.push_back({d, 0}); break;
+    case HMI_BLOCK_ENC_POSTLN:
+    case HMI_BLOCK_DEC_PRELN:
+      out = {{3 * d, d}, {3 * d, 0}, {d, d}, {d, 0}, {d, 0}, {d, 0}};
+      out.insert(out.end(), ffn.begin(), ffn.end());
+      out.push_back({d, 0}); out.push_back({d, 0}); break;
+    case HMI_BLOCK_ADAPTER:
+      out = ffn; break;
+  }
+  return out;
+}
+
+enum { T_W1 = 0, T_B1, T_W2, T_B2, T_LNG, T_LNB };                      // FFN / ADAPTER
+enum { A_WQKV = 0, A_BQKV, A_WO, A_BO, A_LN1G, A_LN1B, A_W1, A_B1, A_W2, A_B2, A_LN2G, A_LN2B };
+
+void free_all(hmi_pool* p) {
+  (void)hipStreamSynchronize(p->compute);
+  if (p->copy) (void)hipStreamSynchronize(p->copy);
+  (void)hipFree(p->d_pool);
+  (void)hipFree(p->d_idx);
+  (void)hipFree(p->w_qkv); (void)hipFree(p->w_ctx); (void)hipFree(p->w_hmid);
+  (void)hipFree(p->w_act); (void)hipFree(p->w_z); (void)hipFree(p->w_x1);
+  (void)hipFree(p->w_y32); (void)hipFree(p->w_yst);
+  for (char* a : p->arenas) (void)hipHostFree(a);
+  for (int i = 0; i < 2; ++i) {
+    if (p->stage[i]) (void)hipHostFree(p->stage[i]);
+    if (p->stage_ev[i]) (void)hipEventDestroy(p->stage_ev[i]);
+  }
+  for (int i = 0; i < 4; ++i) {
+    if (p->h_idx[i]) (void)hipHostFree(p->h_idx[i]);
+    if (p->idx_ev[i]) (void)hipEventDestroy(p->idx_ev[i]);
+  }
+  for (auto& sp : p->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+  p->fwd_done.destroy();
+  p->copy_done.destroy();
+  if (p->copy) (void)hipStreamDestroy(p->copy);
+  delete p;
+}
+
+// Make the copy stream wait until every forward that read `slot` has finished.
+void copy_waits_for_slot_readers(hmi_pool* p, int slot) {
+  const uint64_t need = p->slot_fwd[slot];
+  if (need > p->copy_waited_fwd) {
+    (void)hipStreamWaitEvent(p->copy, p->fwd_done.at_least(need), 0);
+    p->copy_waited_fwd = need;
+  }
+}
+
+// Take a slot for `tenant`: a free one, else the least recently used slot whose stamp is
+// older than `protect_from` (slots stamped at or after it belong to the batch being set
+// up).  Ties on the stamp go to the lowest tenant id.  Returns -1 if none.
+int acquire_slot(hmi_pool* p, int tenant, uint64_t protect_from) {
+  int slot = -1;
+  if (!p->free_slots.empty()) {
+    slot = p->free_slots.back();
+    p->free_slots.pop_back();
+  } else {
+    if (!p->cfg.host_tier) return -1;
+    uint64_t best_stamp = ~0ull;
+    int best_tenant = 0;
+    for (int s = 0; s < p->cfg.hbm_slots; ++s) {
+      const uint64_t st = p->slot_stamp[s];
+      if (st >= protect_from) continue;
+      const int tn = p->tenant_of_slot[s];
+      if (st < best_stamp || (st == best_stamp && tn < best_tenant)) {
+        best_stamp = st; best_tenant = tn; slot = s;
+      }
+    }
+    if (slot < 0) return -1;
+    p->slot_of_tenant[p->tenant_of_slot[slot]] = -1;
+    ++p->evictions;
+  }
+  p->tenant_of_slot[slot] = tenant;
+  p->slot_of_tenant[tenant] = slot;
+  for (int l = 0; l < p->cfg.n_layers; ++l) p->slot_valid[(size_t)slot * p->cfg.n_layers + l] = 0;
+  return slot;
+}
+
+// Enqueue pinned-host -> HBM copy of one (tenant, layer) image on the copy stream.
+int32_t enqueue_swap_in(hmi_pool* p, int tenant, int slot, int layer) {
+  copy_waits_for_slot_readers(p, slot);
+  const char* src = p->host_img[tenant] + (size_t)layer * p->image_bytes;
+  char* dst = p->d_pool + (size_t)slot * p->slot_stride + (size_t)layer * p->image_bytes;
+  HIP_TRY(p, hipMemcpyAsync(dst, src, p->image_bytes, hipMemcpyHostToDevice, p->copy));
+  p->slot_valid[(size_t)slot * p->cfg.n_layers + layer] = 1;
+  p->slot_copy[slot] = p->copy_done.next;  // the record() that follows this batch of copies
+  p->bytes_h2d += (int64_t)p->image_bytes;
+  return HMI_OK;
+}
+
+// Brackets one kernel launch with timing events when profiling is on.
+struct ProfSpan {
+  hmi_pool* p; hipEvent_t b = nullptr;
+  ProfSpan(hmi_pool* pool, int kind) : p(pool) {
+    if (!p->profiling || p->spans.size() >= 65536) return;
+    hipEvent_t a;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); b = nullptr; return; }
+    (void)hipEventRecord(a, p->compute);
+    p->spans.push_back({kind, a, b});
+  }
+  ~ProfSpan() { if (b) (void)hipEventRecord(b, p->compute); }
+};
+
+int bits_for(int n) {
+  int b = 1;
+  while ((1ll << b) < n) ++b;
+  return (b + 3) / 4 * 4;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
+  if (!cfg || !out) return fail(nullptr, HMI_ERR_ARG, "null config or out pointer");
+  const hmi_pool_config_t& c = *cfg;
+  if (c.block < HMI_BLOCK_FFN || c.block > HMI_BLOCK_ADAPTER) return fail(nullptr, HMI_ERR_ARG, "bad block %d", c.block);
+  if (c.dtype != HMI_F32 && c.dtype != HMI_BF16) return fail(nullptr, HMI_ERR_ARG, "bad dtype %d", c.dtype);
+  const int mult = c.dtype == HMI_BF16 ? 64 : 16;
+  if (c.d_model <= 0 || c.d_ff <= 0 || c.d_model % mult || c.d_ff % mult || c.d_model > 2048)
+    return fail(nullptr, HMI_ERR_ARG, "d_model/d_ff must be positive multiples of %d (d_model <= 2048)", mult);
+  const bool attn = c.block == HMI_BLOCK_ENC_POSTLN || c.block == HMI_BLOCK_DEC_PRELN;
+  if (attn) {
+    if (c.n_heads <= 0 || c.d_model % c.n_heads) return fail(nullptr, HMI_ERR_ARG, "n_heads must divide d_model");
+    const int dh = c.d_model / c.n_heads;
+    if (c.dtype == HMI_BF16 ? dh != 64 : dh > 64) return fail(nullptr, HMI_ERR_ARG, "d_head must be 64 (bf16) or <= 64 (f32)");
+  }
+  if (c.n_layers < 1 || c.max_tenants < 1 || c.hbm_slots < 1 || c.hbm_slots > c.max_tenants)
+    return fail(nullptr, HMI_ERR_ARG, "need n_layers >= 1 and 1 <= hbm_slots <= max_tenants");
+  if (c.max_requests < 1 || c.max_requests > kMaxRequests || c.max_tokens < c.max_requests)
+    return fail(nullptr, HMI_ERR_ARG, "need 1 <= max_requests <= %d and max_tokens >= max_requests", kMaxRequests);
+  if (!c.host_tier && c.hbm_slots != c.max_tenants)
+    return fail(nullptr, HMI_ERR_ARG, "without host_tier every tenant needs a slot: hbm_slots must equal max_tenants");
+  if (!(c.ln_eps >= 0.0f)) return fail(nullptr, HMI_ERR_ARG, "ln_eps must be >= 0");
+
+  hmi_pool* p = new (std::nothrow) hmi_pool();
+  if (!p) return fail(nullptr, HMI_ERR_OOM, "host allocation failed");
+  p->cfg = c;
+  p->bf16 = c.dtype == HMI_BF16;
+  p->esize = p->bf16 ? 2 : 4;
+  p->tile_m = p->bf16 ? 256 : 64;
+  size_t off = 0;
+  for (auto& sh : tensor_shapes(c)) {
+    const size_t bytes = (size_t)sh.first * (sh.second ? sh.second : 1) * p->esize;
+    p->tl.push_back({off, bytes});
+    off = align_up(off + bytes, kAlign);
+  }
+  p->image_bytes = off;
+  p->slot_stride = off * c.n_layers;
+
+#define CREATE_TRY(call)                                                                        \
+  do {                                                                                          \
+    hipError_t e_ = (call);                                                                     \
+    if (e_ != hipSuccess) {                                                                     \
+      int32_t rc = fail(nullptr, e_ == hipErrorOutOfMemory ? HMI_ERR_OOM : HMI_ERR_DEVICE,      \
+                        "%s failed: %s", #call, hipGetErrorString(e_));                         \
+      free_all(p);                                                                              \
+      return rc;                                                                                \
+    }                                                                                           \
+  } while (0)
+
+  CREATE_TRY(hipSetDevice(c.device));
+  p->compute = reinterpret_cast<hipStream_t>(c.compute_stream);
+  CREATE_TRY(hipStreamCreateWithFlags(&p->copy, hipStreamNonBlocking));
+  if (!p->fwd_done.init() || !p->copy_done.init()) {
+    free_all(p);
+    return fail(nullptr, HMI_ERR_DEVICE, "event creation failed");
+  }
+  CREATE_TRY(hipMalloc(&p->d_pool, p->slot_stride * (size_t)c.hbm_slots));
+
+  p->slot_of_tenant.assign(c.max_tenants, -1);
+  p->tenant_of_slot.assign(c.hbm_slots, -1);
+  p->loaded.assign((size_t)c.max_tenants * c.n_layers, 0);
+  p->slot_valid.assign((size_t)c.hbm_slots * c.n_layers, 0);
+  p->slot_stamp.assign(c.hbm_slots, 0);
+  p->slot_fwd.assign(c.hbm_slots, 0);
+  p->slot_copy.assign(c.hbm_slots, 0);
+  for (int s = c.hbm_slots - 1; s >= 0; --s) p->free_slots.push_back(s);
+  if (c.host_tier) p->host_img.assign(c.max_tenants, nullptr);
+  p->mark.assign(c.max_tenants, 0);
+  p->tok_count.assign(c.max_tenants, 0);
+
+  if (!c.host_tier) {
+    for (int i = 0; i < 2; ++i) {
+      CREATE_TRY(hipHostMalloc(&p->stage[i], p->image_bytes, hipHostMallocDefault));
+      CREATE_TRY(hipEventCreateWithFlags(&p->stage_ev[i], hipEventDisableTiming));
+    }
+  }
+  const int Rm = c.max_requests;
+  for (int i = 0; i < 4; ++i) {
+    CREATE_TRY(hipHostMalloc(&p->h_idx[i], sizeof(int32_t) * 3 * Rm, hipHostMallocDefault));
+    CREATE_TRY(hipEventCreateWithFlags(&p->idx_ev[i], hipEventDisableTiming));
+  }
+
+  // device routing arrays, one allocation
+  const size_t MT = (size_t)c.max_tokens;
+  const size_t max_tiles = MT / p->tile_m + Rm + 1;
+  size_t n_i32 = 3 * (size_t)Rm            // ids, lens, req_slot
+                 + Rm + (Rm + 1)           // perm, tok_off
+                 + 2 * (size_t)Rm          // seg_tenant, seg_slot
+                 + 2 * ((size_t)Rm + 1)    // seg_req_off, seg_tok_off
+                 + MT                      // row_src
+                 + 2 * max_tiles + 4;      // tile lists + counters
+  CREATE_TRY(hipMalloc(&p->d_idx, n_i32 * sizeof(int32_t)));
+  CREATE_TRY(hipMemset(p->d_idx, 0, n_i32 * sizeof(int32_t)));
+  int32_t* q = p->d_idx;
+  auto take = [&](size_t n) { int32_t* r = q; q += n; return r; };
+  Route& rt = p->rt;
+  rt.tenant_ids = take(Rm); rt.seq_lens = take(Rm); rt.req_slot = take(Rm);
+  rt.perm = take(Rm); rt.tok_off = take(Rm + 1);
+  rt.seg_tenant = take(Rm); rt.seg_slot = take(Rm);
+  rt.seg_req_off = take(Rm + 1); rt.seg_tok_off = take(Rm + 1);
+  rt.row_src = take(MT);
+  rt.tile_seg[0] = take(max_tiles); rt.tile_row0[0] = take(max_tiles);
+  rt.n_segments = take(1); rt.n_tiles[0] = take(1); rt.n_tiles[1] = take(1);
+  rt.tile_seg[1] = nullptr; rt.tile_row0[1] = nullptr;
+  rt.tile_m[0] = p->tile_m; rt.tile_m[1] = 0;
+  rt.key_bits = bits_for(c.max_tenants);
+
+  const size_t d = c.d_model, f = c.d_ff, es = p->esize;
+  CREATE_TRY(hipMalloc(&p->w_hmid, MT * f * es));
+  if (c.block == HMI_BLOCK_FFN) {
+    CREATE_TRY(hipMalloc(&p->w_z, MT * d * sizeof(float)));
+  } else if (attn) {
+    CREATE_TRY(hipMalloc(&p->w_qkv, MT * 3 * d * es));
+    CREATE_TRY(hipMalloc(&p->w_ctx, MT * d * es));
+    CREATE_TRY(hipMalloc(&p->w_act, MT * d * es));
+    CREATE_TRY(hipMalloc(&p->w_z, MT * d * sizeof(float)));
+    CREATE_TRY(hipMalloc(&p->w_x1, MT * d * sizeof(float)));
+  }
+  if (c.n_layers > 1) {
+    CREATE_TRY(hipMalloc(&p->w_y32, MT * d * sizeof(float)));
+    CREATE_TRY(hipMalloc(&p->w_yst, MT * d * es));
+  }
+#undef CREATE_TRY
+  *out = p;
+  return HMI_OK;
+}
+
+int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
+                             const void* const* tensors, int32_t n_tensors) {
+  if (!p) return HMI_ERR_ARG;
+  if (!tensors) return fail(p, HMI_ERR_ARG, "null tensor list");
+  if (tenant < 0 || tenant >= p->cfg.max_tenants) return fail(p, HMI_ERR_TENANT, "tenant %d outside [0,%d)", tenant, p->cfg.max_tenants);
+  if (layer < 0 || layer >= p->cfg.n_layers) return fail(p, HMI_ERR_ARG, "layer %d outside [0,%d)", layer, p->cfg.n_layers);
+  if (n_tensors != (int32_t)p->tl.size()) return fail(p, HMI_ERR_SHAPE, "block needs %d tensors, got %d", (int)p->tl.size(), n_tensors);
+  for (int i = 0; i < n_tensors; ++i)
+    if (!tensors[i]) return fail(p, HMI_ERR_ARG, "tensor %d is null", i);
+  HIP_TRY(p, hipSetDevice(p->cfg.device));
+  const int L = p->cfg.n_layers;
+
+  if (p->cfg.host_tier) {
+    if (!p->host_img[tenant]) {
+      if (p->arena_left == 0) {
+        char* a = nullptr;
+        HIP_TRY(p, hipHostMalloc(&a, p->slot_stride * (size_t)kArenaImages, hipHostMallocDefault));
+        p->arenas.push_back(a);
+        p->arena_cur = a;
+        p->arena_left = kArenaImages;
+      }
+      p->host_img[tenant] = p->arena_cur;
+      p->arena_cur += p->slot_stride;
+      --p->arena_left;
+    }
+    int slot = p->slot_of_tenant[tenant];
+    if (slot >= 0 && p->slot_valid[(size_t)slot * L + layer]) {
+      // replacing weights that may be in use or in flight: drain both streams first
+      HIP_TRY(p, hipStreamSynchronize(p->compute));
+      HIP_TRY(p, hipStreamSynchronize(p->copy));
+    }
+    char* img = p->host_img[tenant] + (size_t)layer * p->image_bytes;
+    for (int i = 0; i < n_tensors; ++i) memcpy(img + p->tl[i].off, tensors[i], p->tl[i].bytes);
+    p->loaded[(size_t)tenant * L + layer] = 1;
+    if (slot < 0 && !p->free_slots.empty()) slot = acquire_slot(p, tenant, 0);
+    if (slot >= 0) {
+      int32_t rc = enqueue_swap_in(p, tenant, slot, layer);
+      if (rc != HMI_OK) return rc;
+      p->bytes_h2d -= (int64_t)p->image_bytes;  // initial placement is not swap traffic
+      p->copy_done.record(p->copy);
+    }
+    return HMI_OK;
+  }
+
+  int slot = p->slot_of_tenant[tenant];
+  if (slot < 0) {
+    slot = acquire_slot(p, tenant, 0);
+    if (slot < 0) return fail(p, HMI_ERR_CAPACITY, "no HBM slot left for tenant %d", tenant);
+  } else if (p->slot_valid[(size_t)slot * L + layer]) {
+    HIP_TRY(p, hipStreamSynchronize(p->compute));
+  }
+  const int si = p->stage_i;
+  p->stage_i ^= 1;
+  HIP_TRY(p, hipEventSynchronize(p->stage_ev[si]));  // staging buffer free again
+  for (int i = 0; i < n_tensors; ++i) memcpy(p->stage[si] + p->tl[i].off, tensors[i], p->tl[i].bytes);
+  char* dst = p->d_pool + (size_t)slot * p->slot_stride + (size_t)layer * p->image_bytes;
+  HIP_TRY(p, hipMemcpyAsync(dst, p->stage[si], p->image_bytes, hipMemcpyHostToDevice, p->copy));
+  HIP_TRY(p, hipEventRecord(p->stage_ev[si], p->copy));
+  p->slot_copy[slot] = p->copy_done.next;
+  p->copy_done.record(p->copy);
+  p->slot_valid[(size_t)slot * L + layer] = 1;
+  p->loaded[(size_t)tenant * L + layer] = 1;
+  return HMI_OK;
+}
+
+int32_t hmi_pool_prefetch(hmi_pool_t* p, int32_t layer, const int32_t* ids, int32_t n) {
+  if (!p) return HMI_ERR_ARG;
+  if (n < 0 || (n > 0 && !ids)) return fail(p, HMI_ERR_ARG, "bad tenant list");
+  if (layer < 0 || layer >= p->cfg.n_layers) return fail(p, HMI_ERR_ARG, "layer %d outside [0,%d)", layer, p->cfg.n_layers);
+  if (!p->cfg.host_tier || n == 0) return HMI_OK;
+  HIP_TRY(p, hipSetDevice(p->cfg.device));
+  const int L = p->cfg.n_layers;
+  for (int i = 0; i < n; ++i) {
+    const int t = ids[i];
+    if (t < 0 || t >= p->cfg.max_tenants || !p->loaded[(size_t)t * L + layer])
+      return fail(p, HMI_ERR_TENANT, "tenant %d (layer %d) is not loaded", t, layer);
+  }
+  const uint64_t now = ++p->clock;
+  for (int i = 0; i < n; ++i) {  // keep what is already here
+    const int s = p->slot_of_tenant[ids[i]];
+    if (s >= 0) p->slot_stamp[s] = now;
+  }
+  bool copied = false;
+  for (int i = 0; i < n; ++i) {
+    const int t = ids[i];
+    int s = p->slot_of_tenant[t];
+    if (s < 0) {
+      s = acquire_slot(p, t, now);
+      if (s < 0) break;  // best effort
+      p->slot_stamp[s] = now;
+    }
+    if (!p->slot_valid[(size_t)s * L + layer]) {
+      int32_t rc = enqueue_swap_in(p, t, s, layer);
+      if (rc != HMI_OK) return rc;
+      copied = true;
+    }
+  }
+  if (copied) p->copy_done.record(p->copy);
+  return HMI_OK;
+}
+
+int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
+                          const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
+  if (!p) return HMI_ERR_ARG;
+  if (R == 0) return HMI_OK;
+  if (R < 0 || !x || !y || !tenant_ids || !seq_lens) return fail(p, HMI_ERR_ARG, "null pointer or negative request count");
+  if (x == y) return fail(p, HMI_ERR_ARG, "x and y must be different buffers");
+  if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
+    return fail(p, HMI_ERR_ARG, "layers [%d,%d) outside [0,%d)", layer_begin, layer_end, p->cfg.n_layers);
+  if (R > p->cfg.max_requests) return fail(p, HMI_ERR_SHAPE, "%d requests > max_requests %d", R, p->cfg.max_requests);
+  const hmi_pool_config_t& c = p->cfg;
+  const int L = c.n_layers;
+
+  // ---- validate, count tokens per distinct tenant
+  if (++p->epoch == 0) { std::fill(p->mark.begin(), p->mark.end(), 0u); p->epoch = 1; }
+  p->distinct.clear();
+  int64_t N = 0;
+  int max_len = 0;
+  for (int r = 0; r < R; ++r) {
+    const int t = tenant_ids[r], len = seq_lens[r];
+    if (len <= 0) return fail(p, HMI_ERR_SHAPE, "seq_lens[%d] = %d", r, len);
+    if (t < 0 || t >= c.max_tenants) return fail(p, HMI_ERR_TENANT, "tenant_ids[%d] = %d outside [0,%d)", r, t, c.max_tenants);
+    for (int l = layer_begin; l < layer_end; ++l)
+      if (!p->loaded[(size_t)t * L + l]) return fail(p, HMI_ERR_TENANT, "tenant %d (layer %d) was never loaded", t, l);
+    if (p->mark[t] != p->epoch) { p->mark[t] = p->epoch; p->tok_count[t] = 0; p->distinct.push_back(t); }
+    p->tok_count[t] += len;
+    N += len;
+    max_len = std::max(max_len, len);
+    if (N > c.max_tokens) return fail(p, HMI_ERR_SHAPE, "batch has more than max_tokens = %d tokens", c.max_tokens);
+  }
+  const int G = (int)p->distinct.size();
+  if (G > c.hbm_slots) return fail(p, HMI_ERR_CAPACITY, "%d distinct tenants in one batch > hbm_slots %d", G, c.hbm_slots);
+  HIP_TRY(p, hipSetDevice(c.device));
+
+  // ---- residency of the first layer: hits first (so they cannot be chosen as victims)
+  const uint64_t now = ++p->clock;
+  int n_mtiles = 0;
+  for (int t : p->distinct) {
+    n_mtiles += (p->tok_count[t] + p->tile_m - 1) / p->tile_m;
+    const int s = p->slot_of_tenant[t];
+    if (s >= 0) p->slot_stamp[s] = now;
+  }
+  // Brings `layer` of every tenant of the batch into HBM (copy stream); returns the copy
+  // sequence the compute stream has to wait for before reading those weights.
+  auto make_resident = [&](int layer, bool count, uint64_t* need_out) -> int32_t {
+    bool copied = false;
+    uint64_t need = 0;
+    for (int t : p->distinct) {
+      int s = p->slot_of_tenant[t];
+      const bool hit = s >= 0 && p->slot_valid[(size_t)s * L + layer];
+      if (count) { if (hit) ++p->hits; else ++p->misses; }
+      if (s < 0) {
+        s = acquire_slot(p, t, now);
+        if (s < 0) return fail(p, HMI_ERR_CAPACITY, "no evictable HBM slot for tenant %d", t);
+        p->slot_stamp[s] = now;
+      }
+      if (!p->slot_valid[(size_t)s * L + layer]) {
+        int32_t rc = enqueue_swap_in(p, t, s, layer);
+        if (rc != HMI_OK) return rc;
+        copied = true;
+      }
+      need = std::max(need, p->slot_copy[s]);
+    }
+    if (copied) p->copy_done.record(p->copy);
+    *need_out = need;
+    return HMI_OK;
+  };
+  uint64_t need_copy = 0;
+  {
+    int32_t rc = make_resident(layer_begin, true, &need_copy);
+    if (rc != HMI_OK) return rc;
+  }
+
+  // ---- index arrays to the device
+  const int bi = p->idx_i;
+  p->idx_i = (p->idx_i + 1) & 3;
+  HIP_TRY(p, hipEventSynchronize(p->idx_ev[bi]));
+  int32_t* h = p->h_idx[bi];
+  const int Rm = c.max_requests;
+  for (int r = 0; r < R; ++r) {
+    h[r] = tenant_ids[r];
+    h[Rm + r] = seq_lens[r];
+    h[2 * Rm + r] = p->slot_of_tenant[tenant_ids[r]];
+  }
+  hipStream_t s = p->compute;
+  HIP_TRY(p, hipMemcpyAsync(const_cast<int32_t*>(p->rt.tenant_ids), h, sizeof(int32_t) * 3 * Rm,
+                            hipMemcpyHostToDevice, s));
+  HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
+
+  const Route& rt = p->rt;
+  { ProfSpan ps(p, HMI_KERNEL_ROUTER); launch_router(rt, R, s); }
+  p->last_R = R;
+
+  const int d = c.d_model, f = c.d_ff;
+  const bool f32 = !p->bf16;  // fp32 pools: "storage" and fp32 coincide
+
+  // Between the layers of one call the activations stay in fp32 (w_y32, residual operand)
+  // next to a storage-dtype copy (w_yst, GEMM operand); only the last layer rounds into y.
+  const void* in_st = x;        // layer input, storage dtype
+  const void* in_res = x;       // layer input as residual / LayerNorm operand
+  bool in_res_f32 = f32;
+
+  for (int layer = layer_begin; layer < layer_end; ++layer) {
+    const bool last = layer + 1 == layer_end;
+    // weights of this layer must have landed before the first kernel that reads them
+    if (need_copy > p->compute_waited_copy) {
+      HIP_TRY(p, hipStreamWaitEvent(s, p->copy_done.at_least(need_copy), 0));
+      p->compute_waited_copy = need_copy;
+    }
+    // fine-grained pipelining (Sec. 6.2): start the next layer's swap-in before this
+    // layer's kernels are enqueued, so that the copies run under them
+    uint64_t need_next = 0;
+    if (!last) {
+      int32_t rc = make_resident(layer + 1, true, &need_next);
+      if (rc != HMI_OK) return rc;
+    }
+
+    const size_t lay = (size_t)layer * p->image_bytes;
+    auto gemm = [&](const void* A, int lda, int tw, int tb, int n_out, int k, int epi, void* C, int ldc,
+                    const void* resid, int ldr, bool resid_f32, bool out_f32, void* C2) {
+      GemmArgs g{};
+      g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.resid = resid; g.ldr = ldr;
+      g.resid_f32 = resid_f32; g.out_f32 = out_f32; g.C2 = C2;
+      g.pool = p->d_pool; g.slot_stride = p->slot_stride;
+      g.w_off = lay + p->tl[tw].off; g.b_off = lay + p->tl[tb].off;
+      g.n_out = n_out; g.k = k; g.epi = epi; g.which_tiles = 0; g.n_mtiles = n_mtiles;
+      ProfSpan ps(p, HMI_KERNEL_GEMM);
+      if (p->bf16) launch_gemm_bf16(g, rt, s); else launch_gemm_f32(g, rt, s);
+    };
+    auto lnorm = [&](const void* in, bool in_f32, float* out_f32, void* out_st, int tg, int tb) {
+      LnArgs a{};
+      a.in = in; a.in_f32 = in_f32; a.out_f32 = out_f32; a.out_st = out_st;
+      a.pool = p->d_pool; a.slot_stride = p->slot_stride;
+      a.g_off = lay + p->tl[tg].off; a.b_off = lay + p->tl[tb].off;
+      a.d = d; a.eps = c.ln_eps; a.n_rows = (int)N; a.bf16 = p->bf16;
+      ProfSpan ps(p, HMI_KERNEL_LAYERNORM);
+      launch_layernorm(a, rt, s);
+    };
+    auto attention = [&](bool causal) {
+      AttnArgs a{};
+      a.qkv = p->w_qkv; a.ctx = p->w_ctx; a.d = d; a.n_heads = c.n_heads; a.causal = causal;
+      a.R = R; a.max_len = max_len; a.bf16 = p->bf16; a.n_rows = (int)N;
+      ProfSpan ps(p, HMI_KERNEL_ATTENTION);
+      launch_attention(a, rt, s);
+    };
+
+    switch (c.block) {
+      case HMI_BLOCK_FFN:
+        gemm(in_st, d, T_W1, T_B1, f, d, EPI_BIAS_GELU, p->w_hmid, f, nullptr, 0, false, false, nullptr);
+        gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, p->w_z, d, in_res, d, in_res_f32, true, nullptr);
+        lnorm(p->w_z, true, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, T_LNG, T_LNB);
+        break;
+      case HMI_BLOCK_ADAPTER:
+        gemm(in_st, d, T_W1, T_B1, f, d, EPI_BIAS_RELU, p->w_hmid, f, nullptr, 0, false, false, nullptr);
+        if (last)
+          gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, y, d, in_res, d, in_res_f32, f32, nullptr);
+        else
+          gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, p->w_y32, d, in_res, d, in_res_f32, true, p->w_yst);
+        break;
+      case HMI_BLOCK_ENC_POSTLN:
+        gemm(in_st, d, A_WQKV, A_BQKV, 3 * d, d, EPI_BIAS, p->w_qkv, 3 * d, nullptr, 0, false, false, nullptr);
+        attention(false);
+        gemm(p->w_ctx, d, A_WO, A_BO, d, d, EPI_BIAS_RESID, p->w_z, d, in_res, d, in_res_f32, true, nullptr);
+        lnorm(p->w_z, true, p->w_x1, p->bf16 ? p->w_act : nullptr, A_LN1G, A_LN1B);
+        gemm(p->bf16 ? (const void*)p->w_act : (const void*)p->w_x1, d, A_W1, A_B1, f, d, EPI_BIAS_GELU,
+             p->w_hmid, f, nullptr, 0, false, false, nullptr);
+        gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_z, d, p->w_x1, d, true, true, nullptr);
+        lnorm(p->w_z, true, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, A_LN2G, A_LN2B);
+        break;
+      case HMI_BLOCK_DEC_PRELN:
+        lnorm(in_res, in_res_f32, nullptr, p->w_act, A_LN1G, A_LN1B);
+        gemm(p->w_act, d, A_WQKV, A_BQKV, 3 * d, d, EPI_BIAS, p->w_qkv, 3 * d, nullptr, 0, false, false, nullptr);
+        attention(true);
+        gemm(p->w_ctx, d, A_WO, A_BO, d, d, EPI_BIAS_RESID, p->w_x1, d, in_res, d, in_res_f32, true, nullptr);
+        lnorm(p->w_x1, true, nullptr, p->w_act, A_LN2G, A_LN2B);
+        gemm(p->w_act, d, A_W1, A_B1, f, d, EPI_BIAS_GELU, p->w_hmid, f, nullptr, 0, false, false, nullptr);
+        if (last)
+          gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, y, d, p->w_x1, d, true, f32, nullptr);
+        else
+          gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_y32, d, p->w_x1, d, true, true, nullptr);
+        break;
+    }
+    in_st = p->w_yst;
+    in_res = p->w_y32;
+    in_res_f32 = true;
+    need_copy = need_next;
+  }
+  HIP_TRY(p, hipGetLastError());
+  const uint64_t seq = p->fwd_done.record(s);
+  for (int t : p->distinct) p->slot_fwd[p->slot_of_tenant[t]] = seq;
+  return HMI_OK;
+}
+
+int32_t hmi_layer_forward(hmi_pool_t* p, int32_t layer, const void* x, void* y,
+                          const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
+  return hmi_stack_forward(p, layer, layer + 1, x, y, tenant_ids, seq_lens, R);
+}
+
+int32_t hmi_get_route(hmi_pool_t* p, int32_t* perm, int32_t* seg_tenant, int32_t* seg_req_off,
+                      int32_t* seg_tok_off, int32_t* n_segments) {
+  if (!p) return HMI_ERR_ARG;
+  HIP_TRY(p, hipSetDevice(p->cfg.device));
+  HIP_TRY(p, hipStreamSynchronize(p->compute));
+  const int R = p->last_R;
+  int32_t G = 0;
+  if (R > 0) HIP_TRY(p, hipMemcpy(&G, p->rt.n_segments, sizeof(int32_t), hipMemcpyDeviceToHost));
+  if (n_segments) *n_segments = G;
+  if (R == 0) return HMI_OK;
+  if (perm) HIP_TRY(p, hipMemcpy(perm, p->rt.perm, sizeof(int32_t) * R, hipMemcpyDeviceToHost));
+  if (seg_tenant) HIP_TRY(p, hipMemcpy(seg_tenant, p->rt.seg_tenant, sizeof(int32_t) * G, hipMemcpyDeviceToHost));
+  if (seg_req_off) HIP_TRY(p, hipMemcpy(seg_req_off, p->rt.seg_req_off, sizeof(int32_t) * (G + 1), hipMemcpyDeviceToHost));
+  if (seg_tok_off) HIP_TRY(p, hipMemcpy(seg_tok_off, p->rt.seg_tok_off, sizeof(int32_t) * (G + 1), hipMemcpyDeviceToHost));
+  return HMI_OK;
+}
+
+int32_t hmi_pool_stats(hmi_pool_t* p, int64_t* hits, int64_t* misses, int64_t* bytes_h2d, int64_t* evictions) {
+  if (!p) return HMI_ERR_ARG;
+  if (hits) *hits = p->hits;
+  if (misses) *misses = p->misses;
+  if (bytes_h2d) *bytes_h2d = p->bytes_h2d;
+  if (evictions) *evictions = p->evictions;
+  return HMI_OK;
+}
+
+int32_t hmi_pool_profile(hmi_pool_t* p, int32_t enable) {
+  if (!p) return HMI_ERR_ARG;
+  p->profiling = enable != 0;
+  return HMI_OK;
+}
+
+int32_t hmi_pool_profile_read(hmi_pool_t* p, double* ms, int64_t* launches) {
+  if (!p) return HMI_ERR_ARG;
+  HIP_TRY(p, hipSetDevice(p->cfg.device));
+  HIP_TRY(p, hipStreamSynchronize(p->compute));
+  for (int k = 0; k < HMI_KERNEL_KINDS; ++k) {
+    if (ms) ms[k] = 0.0;
+    if (launches) launches[k] = 0;
+  }
+  for (auto& sp : p->spans) {
+    float t = 0.0f;
+    if (hipEventElapsedTime(&t, sp.a, sp.b) == hipSuccess) {
+      if (ms) ms[sp.kind] += (double)t;
+      if (launches) launches[sp.kind] += 1;
+    }
+    (void)hipEventDestroy(sp.a);
+    (void)hipEventDestroy(sp.b);
+  }
+  p->spans.clear();
+  return HMI_OK;
+}
+
+int64_t hmi_pool_image_bytes(const hmi_pool_t* p) { return p ? (int64_t)p->image_bytes : 0; }
+
+const char* hmi_last_error(const hmi_pool_t* p) { return p ? p->err : g_create_error; }
+
+int32_t hmi_pool_destroy(hmi_pool_t* p) {
+  if (!p) return HMI_OK;
+  (void)hipSetDevice(p->cfg.device);
+  free_all(p);
+  return HMI_OK;
+}
+
+}  // extern "C"

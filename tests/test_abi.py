@@ -1,0 +1,40 @@
+"""The C-ABI library loads and exports every symbol include/hmi.h declares (no compute)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hmi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hmi_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_north_star_calls():
+    syms = declared_symbols()
+    for name in ("hmi_pool_create", "hmi_pool_load_tenant", "hmi_layer_forward", "hmi_pool_destroy"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2504_17449_amd as pkg
+    lib = ctypes.CDLL(pkg.LIB_PATH)
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+    assert sorted(pkg.EXPORTS) == declared_symbols()
+
+
+def test_argument_errors_need_no_gpu():
+    import paper_2504_17449_amd as pkg
+    assert pkg.lib.hmi_pool_create(None, None) == pkg.HMI_ERR_ARG
+    assert "null" in pkg.hmi_last_error(None)
+    assert pkg.hmi_pool_destroy(None) == pkg.HMI_OK
+    assert pkg.lib.hmi_layer_forward(None, 0, None, None, None, None, 0) == pkg.HMI_ERR_ARG
+    rc, h = pkg.hmi_pool_create(block=9, dtype=1, d_model=64, d_ff=64, max_tenants=1,
+                                max_requests=1, max_tokens=1)
+    assert rc == pkg.HMI_ERR_ARG and h is None
+    rc, h = pkg.hmi_pool_create(block=0, dtype=1, d_model=100, d_ff=64, max_tenants=1,
+                                max_requests=1, max_tokens=1)
+    assert rc == pkg.HMI_ERR_ARG and "multiples" in pkg.hmi_last_error(None)

@@ -1,0 +1,171 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded
+inputs.  Routing must be bit-exact; floats within max-abs 2e-2 / relative Frobenius 1e-2
+(bf16) or 1e-4 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import hmi_oracle as O
+from tests.oracle_side import compare, oracle_forward, rows_of
+
+pytestmark = pytest.mark.gpu
+
+
+def check_route(pool, ids, lens):
+    want = O.route(ids, lens)
+    got = pool.route()
+    R = len(ids)
+    assert got["n_segments"] == len(want["seg_tenant"])
+    np.testing.assert_array_equal(got["perm"][:R], want["perm"])
+    np.testing.assert_array_equal(got["seg_tenant"], want["seg_tenant"])
+    np.testing.assert_array_equal(got["seg_req_off"], want["seg_req_off"])
+    np.testing.assert_array_equal(got["seg_tok_off"], want["seg_tok_off"])
+
+
+def run_case(hmi, wl, sample=None, batch=0, tenants="touched"):
+    """Create the pool, load tenants, run all layers, compare ``sample`` requests (default all)."""
+    from paper_2504_17449_amd import harness
+    ids, lens, x = harness.batch_to_device(wl, batch)
+    print(f"case {wl.name} R={len(ids)} N={int(lens.sum())} d={wl.d_model} f={wl.d_ff} "
+          f"dtype={wl.dtype} block={wl.block}", flush=True)
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl, sorted(set(ids.tolist())) if tenants == "touched" else None)
+        cur = torch.empty_like(x)
+        if wl.n_layers == 1:
+            pool.forward(0, x, cur, ids, lens)
+        else:
+            pool.stack_forward(0, wl.n_layers, x, cur, ids, lens)
+        torch.cuda.synchronize()
+        check_route(pool, ids, lens)
+        y_gpu = harness.device_to_f64(cur)
+    finally:
+        pool.close()
+    reqs = list(range(len(ids))) if sample is None else list(sample)
+    y_ref = oracle_forward(wl, ids, lens, reqs, batch)
+    max_abs, rel, ok = compare(y_gpu, y_ref, rows_of(lens, reqs), wl.dtype)
+    print(f"  max_abs={max_abs:.3e} rel_fro={rel:.3e} max|y_ref|={np.nanmax(np.abs(y_ref)):.2f}", flush=True)
+    assert ok, (max_abs, rel)
+    return y_gpu
+
+
+def small(block, dtype, **kw):
+    base = dict(name=f"small_{block}_{dtype}", block=block, dtype=dtype, d_model=128, d_ff=256,
+                n_heads=2, n_layers=1, n_tenants=6, n_requests=20, seq_min=1, seq_max=300,
+                popularity="zipf", zipf_s=1.0, ln_eps=1e-5, hbm_slots=6, host_tier=False, seed=3)
+    base.update(kw)
+    if block in (synth.BLOCK_FFN, synth.BLOCK_ADAPTER):
+        base["n_heads"] = 0
+    return synth.Workload(**base)
+
+
+def test_tiny_fp32_ffn_full_config(hmi):
+    run_case(hmi, synth.WORKLOADS["tiny_fp32"])
+
+
+@pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
+                                   synth.BLOCK_ADAPTER])
+def test_small_fp32_blocks_ragged(hmi, block):
+    run_case(hmi, small(block, "f32", d_model=64, d_ff=128, n_heads=4, seq_max=90))
+
+
+@pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
+                                   synth.BLOCK_ADAPTER])
+def test_small_bf16_blocks_ragged(hmi, block):
+    # seq up to 300: m-tiles of 256 rows with ragged tails, several key blocks, q blocks
+    run_case(hmi, small(block, "bf16"))
+
+
+@pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
+                                   synth.BLOCK_ADAPTER])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_layer_stack_in_one_call(hmi, block, dtype):
+    kw = dict(d_model=64, d_ff=128, n_heads=4) if dtype == "f32" else {}
+    run_case(hmi, small(block, dtype, n_layers=3, seq_max=140, **kw))
+
+
+def test_second_layer_alone(hmi):
+    """forward(layer=1) uses layer 1's weights: equals the oracle fed layer-1 weights only."""
+    from paper_2504_17449_amd import harness
+    from tests.oracle_side import weights_of
+    wl = small(synth.BLOCK_ENC_POSTLN, "bf16", n_layers=2, seq_max=90)
+    ids, lens, x = harness.batch_to_device(wl)
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl)
+        y = torch.empty_like(x)
+        pool.forward(1, x, y, ids, lens)
+        torch.cuda.synchronize()
+        y_gpu = harness.device_to_f64(y)
+    finally:
+        pool.close()
+    X = np.concatenate([synth.hidden_states(wl, r, int(lens[r])) for r in range(len(ids))]).astype(np.float64)
+    y_ref = O.layer_forward(wl.block, X, ids, lens, weights_of(wl, 1), wl.n_heads, wl.ln_eps)
+    _, _, ok = compare(y_gpu, y_ref, np.arange(len(X)), wl.dtype)
+    assert ok
+    y_l0 = O.layer_forward(wl.block, X, ids, lens, weights_of(wl, 0), wl.n_heads, wl.ln_eps)
+    assert np.abs(y_l0 - y_ref).max() > 0.05     # the two layers really differ
+
+
+def test_bf16_adapter_rank_64(hmi):
+    run_case(hmi, small(synth.BLOCK_ADAPTER, "bf16", d_model=768, d_ff=64, seq_max=128, seq_min=128))
+
+
+def test_bert_ffn_full_size_sampled(hmi):
+    wl = synth.WORKLOADS["bert_ffn"]
+    ids, _ = synth.batch_ids_lens(wl)
+    # first and last request of several segments, in arrival order
+    order = np.argsort(ids, kind="stable")
+    sample = sorted(set(order[::9].tolist() + [0, len(ids) - 1]))
+    run_case(hmi, wl, sample=sample, tenants="all")
+
+
+def test_single_request_and_single_tenant(hmi):
+    run_case(hmi, small(synth.BLOCK_ENC_POSTLN, "bf16", n_requests=1, seq_min=5, seq_max=5))
+    run_case(hmi, small(synth.BLOCK_DEC_PRELN, "bf16", n_tenants=1, hbm_slots=1, n_requests=9))
+
+
+def test_same_inputs_same_weights_identical_rows(hmi):
+    """Two requests with identical hidden states routed to the same tenant get bit-identical rows."""
+    from paper_2504_17449_amd import harness
+    wl = small(synth.BLOCK_ENC_POSTLN, "bf16", n_tenants=3, hbm_slots=3)
+    pool = harness.create_pool(wl, max_requests=4, max_tokens=4 * 70)
+    try:
+        harness.load_tenants(pool, wl)
+        x1 = synth.hidden_states(wl, 0, 70)
+        x = harness.host_to_device(np.concatenate([x1, x1, x1, x1]), wl.dtype)
+        y = torch.empty_like(x)
+        pool.forward(0, x, y, [2, 0, 2, 1], [70, 70, 70, 70])
+        torch.cuda.synchronize()
+        yv = y.view(torch.int16).cpu().numpy()
+        assert np.array_equal(yv[0:70], yv[140:210])        # same tenant
+        assert not np.array_equal(yv[0:70], yv[70:140])     # different tenant
+    finally:
+        pool.close()
+
+
+def test_boundary_errors_and_empty_batch(hmi):
+    from paper_2504_17449_amd import harness
+    wl = small(synth.BLOCK_FFN, "bf16", n_tenants=4, hbm_slots=4)
+    pool = harness.create_pool(wl, max_requests=4, max_tokens=64)
+    try:
+        harness.load_tenants(pool, wl, [0, 1])
+        x = torch.zeros(64, wl.d_model, dtype=torch.bfloat16, device="cuda")
+        y = torch.full_like(x, 7.0)
+        assert hmi.hmi_layer_forward(pool.h, 0, x.data_ptr(), y.data_ptr(), [], []) == hmi.HMI_OK
+        cases = [([0, 9], [4, 4], hmi.HMI_ERR_TENANT),      # id out of range
+                 ([0, 2], [4, 4], hmi.HMI_ERR_TENANT),      # never loaded
+                 ([0, 1], [4, 0], hmi.HMI_ERR_SHAPE),       # empty sequence
+                 ([0, 1], [40, 40], hmi.HMI_ERR_SHAPE),     # too many tokens
+                 ([0] * 5, [1] * 5, hmi.HMI_ERR_SHAPE)]     # too many requests
+        for ids, lens, want in cases:
+            assert hmi.hmi_layer_forward(pool.h, 0, x.data_ptr(), y.data_ptr(), ids, lens) == want
+            assert hmi.hmi_last_error(pool.h)
+        assert hmi.hmi_layer_forward(pool.h, 0, x.data_ptr(), x.data_ptr(), [0], [4]) == hmi.HMI_ERR_ARG
+        assert hmi.hmi_layer_forward(pool.h, 3, x.data_ptr(), y.data_ptr(), [0], [4]) == hmi.HMI_ERR_ARG
+        torch.cuda.synchronize()
+        assert bool((y == 7.0).all())                       # y untouched by every failed call
+        assert hmi.hmi_pool_load_tenant(pool.h, 0, 0, [np.zeros(4, np.uint16)]) == hmi.HMI_ERR_SHAPE
+    finally:
+        pool.close()
