@@ -18,11 +18,14 @@
 //     activation panel then share that XCD's L2.
 #include "hmi_kernels.h"
 
+#include <type_traits>
+
 namespace hmi {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk (8 bf16)
 
 constexpr int BK = 64;          // k extent of one LDS stage (8 chunks of 8 bf16)
 constexpr int kXcds = 8;
@@ -34,7 +37,18 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
 }
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+// GELU(x) = x * Phi(x) with erf from the Abramowitz-Stegun 7.1.26 rational form
+// (|error| <= 1.5e-7, far below bf16 resolution), branch-free: one rcp, one exp.
+__device__ __forceinline__ float gelu_erf(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  const float e = 1.0f - p * t * __expf(-z * z);     // erf(|x| / sqrt 2)
+  return 0.5f * x + 0.5f * fabsf(x) * e;             // 0.5 x (1 + sign(x) e)
+}
 
 template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g, Route rt) {
@@ -101,93 +115,112 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g, Rou
   // A wavefront whose rows all lie beyond the tile's row count has nothing to multiply.
   const bool wave_active = wm * WTM < rows;
 
-  uint4 ra[A_IT], rb[B_IT];
+  {
+    u32x4 ra[A_IT], rb[B_IT];
 #pragma unroll
-  for (int i = 0; i < A_IT; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_src[i]);
+    for (int i = 0; i < A_IT; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_src[i]);
 #pragma unroll
-  for (int i = 0; i < B_IT; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i]);
+    for (int i = 0; i < B_IT; ++i) rb[i] = *reinterpret_cast<const u32x4*>(b_src[i]);
 #pragma unroll
-  for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4*>(As + a_dst[i]) = ra[i];
+    for (int i = 0; i < A_IT; ++i) *reinterpret_cast<u32x4*>(As + a_dst[i]) = ra[i];
 #pragma unroll
-  for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4*>(Bs + b_dst[i]) = rb[i];
+    for (int i = 0; i < B_IT; ++i) *reinterpret_cast<u32x4*>(Bs + b_dst[i]) = rb[i];
+  }
   __syncthreads();
 
   const int KT = K / BK;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < KT;
-    if (more) {
-      const int k1 = (kt + 1) * BK;
-#pragma unroll
-      for (int i = 0; i < A_IT; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_src[i] + k1);
-#pragma unroll
-      for (int i = 0; i < B_IT; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + k1);
-    }
-    if (wave_active) {
-      const uint16_t* Ac = As + cur * BM * BK;
-      const uint16_t* Bc = Bs + cur * BN * BK;
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        const int chunk = ks * 2 + lh;
-        bf16x8 fa[TM], fb[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int row = wm * WTM + i * 32 + l32;
-          fa[i] = *reinterpret_cast<const bf16x8*>(Ac + row * BK + ((chunk ^ swz(row)) << 3));
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int row = wn * WTN + j * 32 + l32;
-          fb[j] = *reinterpret_cast<const bf16x8*>(Bc + row * BK + ((chunk ^ swz(row)) << 3));
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-      }
-    }
-    if (more) {
-      uint16_t* An = As + (cur ^ 1) * BM * BK;
-      uint16_t* Bn = Bs + (cur ^ 1) * BN * BK;
-#pragma unroll
-      for (int i = 0; i < A_IT; ++i) *reinterpret_cast<uint4*>(An + a_dst[i]) = ra[i];
-#pragma unroll
-      for (int i = 0; i < B_IT; ++i) *reinterpret_cast<uint4*>(Bn + b_dst[i]) = rb[i];
-    }
-    __syncthreads();
+  // One loop body, expanded with and without the multiply so that neither version has a
+  // branch inside (a branch there lets the compiler sink the prefetch below the MFMAs).
+  // The last iteration re-reads its own k-stage (in bounds) and parks it in the idle
+  // buffer, which also keeps the body branch-free.
+#define HMI_K_LOOP(ACTIVE)                                                                        \
+  for (int kt = 0; kt < KT; ++kt) {                                                               \
+    const int cur = kt & 1;                                                                       \
+    const int k1 = min(kt + 1, KT - 1) * BK;                                                      \
+    u32x4 ra[A_IT], rb[B_IT];                                                                     \
+    _Pragma("unroll") for (int i = 0; i < A_IT; ++i)                                              \
+        ra[i] = *reinterpret_cast<const u32x4*>(a_src[i] + k1);                                   \
+    _Pragma("unroll") for (int i = 0; i < B_IT; ++i)                                              \
+        rb[i] = *reinterpret_cast<const u32x4*>(b_src[i] + k1);                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    if (ACTIVE) {                                                                                 \
+      const uint16_t* Ac = As + cur * BM * BK;                                                    \
+      const uint16_t* Bc = Bs + cur * BN * BK;                                                    \
+      _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                    \
+        const int chunk = ks * 2 + lh;                                                            \
+        bf16x8 fa[TM], fb[TN];                                                                    \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                          \
+          const int row = wm * WTM + i * 32 + l32;                                                \
+          fa[i] = *reinterpret_cast<const bf16x8*>(Ac + row * BK + ((chunk ^ swz(row)) << 3));    \
+        }                                                                                         \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                          \
+          const int row = wn * WTN + j * 32 + l32;                                                \
+          fb[j] = *reinterpret_cast<const bf16x8*>(Bc + row * BK + ((chunk ^ swz(row)) << 3));    \
+        }                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+          _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);\
+      }                                                                                           \
+    }                                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    uint16_t* An = As + (cur ^ 1) * BM * BK;                                                      \
+    uint16_t* Bn = Bs + (cur ^ 1) * BN * BK;                                                      \
+    _Pragma("unroll") for (int i = 0; i < A_IT; ++i)                                              \
+        *reinterpret_cast<u32x4*>(An + a_dst[i]) = ra[i];                                         \
+    _Pragma("unroll") for (int i = 0; i < B_IT; ++i)                                              \
+        *reinterpret_cast<u32x4*>(Bn + b_dst[i]) = rb[i];                                         \
+    __syncthreads();                                                                              \
   }
+  if (wave_active) { HMI_K_LOOP(true) } else { HMI_K_LOOP(false) }
+#undef HMI_K_LOOP
 
   if (!wave_active) return;
 
   // ---- epilogue.  Accumulator register r of tile (i,j) holds
   //      row = 8*(r/4) + 4*(lane/32) + r%4,  column = lane%32.
-  const int epi = g.epi;
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col = n0 + wn * WTN + j * 32 + l32;
-    if (col >= g.n_out) continue;
-    const float bv = bf2f(bias[col]);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = wm * WTM + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-        if (m >= rows) continue;
-        const size_t orow = (size_t)rowsrc_s[m];
-        float v = acc[i][j][r] + bv;
-        if (epi == EPI_BIAS_GELU) v = gelu_erf(v);
-        else if (epi == EPI_BIAS_RELU) v = fmaxf(v, 0.0f);
-        else if (epi == EPI_BIAS_RESID) {
-          v += g.resid_f32 ? reinterpret_cast<const float*>(g.resid)[orow * g.ldr + col]
-                           : bf2f(reinterpret_cast<const uint16_t*>(g.resid)[orow * g.ldr + col]);
-        }
-        if (g.out_f32) reinterpret_cast<float*>(g.C)[orow * g.ldc + col] = v;
-        else reinterpret_cast<uint16_t*>(g.C)[orow * g.ldc + col] = f2bf(v);
-        if (g.C2) reinterpret_cast<uint16_t*>(g.C2)[orow * g.ldc + col] = f2bf(v);
-      }
-    }
+  // The epilogue kind is uniform for the launch: branch once, then straight-line loops.
+#define HMI_EPILOGUE(VALUE_EXPR, STORE_STMT)                                            \
+  _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                      \
+    const int col = n0 + wn * WTN + j * 32 + l32;                                       \
+    if (col < g.n_out) {                                                                \
+      const float bv = bf2f(bias[col]);                                                 \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                  \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                \
+          const int m = wm * WTM + i * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);            \
+          if (m < rows) {                                                               \
+            const size_t orow = (size_t)rowsrc_s[m];                                    \
+            const float a = acc[i][j][r] + bv;                                          \
+            const float v = (VALUE_EXPR);                                               \
+            STORE_STMT;                                                                 \
+          }                                                                             \
+        }                                                                               \
+      }                                                                                 \
+    }                                                                                   \
   }
+#define HMI_ST_BF16 reinterpret_cast<uint16_t*>(g.C)[orow * g.ldc + col] = f2bf(v)
+#define HMI_ST_F32 reinterpret_cast<float*>(g.C)[orow * g.ldc + col] = v
+#define HMI_RES_BF16 bf2f(reinterpret_cast<const uint16_t*>(g.resid)[orow * g.ldr + col])
+#define HMI_RES_F32 reinterpret_cast<const float*>(g.resid)[orow * g.ldr + col]
+  const int epi = g.epi;
+  if (epi == EPI_BIAS) {
+    HMI_EPILOGUE(a, HMI_ST_BF16)
+  } else if (epi == EPI_BIAS_GELU) {
+    HMI_EPILOGUE(gelu_erf(a), HMI_ST_BF16)
+  } else if (epi == EPI_BIAS_RELU) {
+    HMI_EPILOGUE(fmaxf(a, 0.0f), HMI_ST_BF16)
+  } else if (g.C2) {  // residual, fp32 result plus a bf16 copy
+    if (g.resid_f32) { HMI_EPILOGUE(a + HMI_RES_F32, HMI_ST_F32; reinterpret_cast<uint16_t*>(g.C2)[orow * g.ldc + col] = f2bf(v)) }
+    else { HMI_EPILOGUE(a + HMI_RES_BF16, HMI_ST_F32; reinterpret_cast<uint16_t*>(g.C2)[orow * g.ldc + col] = f2bf(v)) }
+  } else if (g.out_f32) {
+    if (g.resid_f32) { HMI_EPILOGUE(a + HMI_RES_F32, HMI_ST_F32) } else { HMI_EPILOGUE(a + HMI_RES_BF16, HMI_ST_F32) }
+  } else {
+    if (g.resid_f32) { HMI_EPILOGUE(a + HMI_RES_F32, HMI_ST_BF16) } else { HMI_EPILOGUE(a + HMI_RES_BF16, HMI_ST_BF16) }
+  }
+#undef HMI_EPILOGUE
+#undef HMI_ST_BF16
+#undef HMI_ST_F32
+#undef HMI_RES_BF16
+#undef HMI_RES_F32
 }
 
 template <int BM, int BN, int WM, int WN>
