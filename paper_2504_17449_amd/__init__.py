@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhmi.so")
+LIB_PATH = os.environ.get("HMI_LIB_PATH") or os.path.join(_HERE, "libhmi.so")  # override: alternative builds
 
 HMI_OK, HMI_ERR_ARG, HMI_ERR_OOM, HMI_ERR_TENANT, HMI_ERR_SHAPE, HMI_ERR_CAPACITY, HMI_ERR_DEVICE = \
     0, -1, -2, -3, -4, -5, -6

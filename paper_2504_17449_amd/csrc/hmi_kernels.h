@@ -53,13 +53,15 @@ struct GemmArgs {
   size_t w_off, b_off;                // byte offsets of W and bias inside a slot (layer included)
   int n_out, k;
   int epi;
-  int which_tiles;                    // index into Route::tile_* (tile height)
-  int n_mtiles;                       // exact count, computed on the host
+  int n_mtiles_list[2];               // exact m-tile counts of both tile lists, computed on the host
+  int which_tiles;                    // set by the launcher: index into Route::tile_* ...
+  int n_mtiles;                       // ... and that list's count
 };
 
 void launch_gemm_bf16(const GemmArgs& g, const Route& rt, hipStream_t s);
 void launch_gemm_f32(const GemmArgs& g, const Route& rt, hipStream_t s);
-int  gemm_bf16_tile_m(int n_out, int k);  // tile height the bf16 kernel will use for this shape
+constexpr int kBf16TileM0 = 256, kBf16TileM1 = 128;  // heights of the two m-tile lists of bf16 pools
+constexpr int kF32TileM = 64;
 
 // Row LayerNorm with per-tenant gain/shift looked up through the route.
 // in: fp32 (in_f32) or storage dtype; writes out_f32 (fp32, may be null) and/or

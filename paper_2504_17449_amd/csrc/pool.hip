@@ -100,7 +100,7 @@ struct hmi_pool {
   int32_t* d_idx = nullptr;   // all device int32 routing arrays, one allocation
   Route rt{};
   int last_R = 0;
-  int tile_m = 256;
+  int tile_m[2] = {256, 128};
 
   // workspaces
   char *w_qkv = nullptr, *w_ctx = nullptr, *w_hmid = nullptr, *w_act = nullptr;
@@ -288,7 +288,8 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   p->cfg = c;
   p->bf16 = c.dtype == HMI_BF16;
   p->esize = p->bf16 ? 2 : 4;
-  p->tile_m = p->bf16 ? 256 : 64;
+  p->tile_m[0] = p->bf16 ? kBf16TileM0 : kF32TileM;
+  p->tile_m[1] = p->bf16 ? kBf16TileM1 : 0;
   size_t off = 0;
   for (auto& sh : tensor_shapes(c)) {
     const size_t bytes = (size_t)sh.first * (sh.second ? sh.second : 1) * p->esize;
@@ -344,13 +345,14 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
 
   // device routing arrays, one allocation
   const size_t MT = (size_t)c.max_tokens;
-  const size_t max_tiles = MT / p->tile_m + Rm + 1;
+  const size_t max_tiles0 = MT / p->tile_m[0] + Rm + 1;
+  const size_t max_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + Rm + 1 : 0;
   size_t n_i32 = 3 * (size_t)Rm            // ids, lens, req_slot
                  + Rm + (Rm + 1)           // perm, tok_off
                  + 2 * (size_t)Rm          // seg_tenant, seg_slot
                  + 2 * ((size_t)Rm + 1)    // seg_req_off, seg_tok_off
                  + MT                      // row_src
-                 + 2 * max_tiles + 4;      // tile lists + counters
+                 + 2 * (max_tiles0 + max_tiles1) + 4;  // tile lists + counters
   CREATE_TRY(hipMalloc(&p->d_idx, n_i32 * sizeof(int32_t)));
   CREATE_TRY(hipMemset(p->d_idx, 0, n_i32 * sizeof(int32_t)));
   int32_t* q = p->d_idx;
@@ -361,10 +363,11 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   rt.seg_tenant = take(Rm); rt.seg_slot = take(Rm);
   rt.seg_req_off = take(Rm + 1); rt.seg_tok_off = take(Rm + 1);
   rt.row_src = take(MT);
-  rt.tile_seg[0] = take(max_tiles); rt.tile_row0[0] = take(max_tiles);
+  rt.tile_seg[0] = take(max_tiles0); rt.tile_row0[0] = take(max_tiles0);
+  rt.tile_seg[1] = max_tiles1 ? take(max_tiles1) : nullptr;
+  rt.tile_row0[1] = max_tiles1 ? take(max_tiles1) : nullptr;
   rt.n_segments = take(1); rt.n_tiles[0] = take(1); rt.n_tiles[1] = take(1);
-  rt.tile_seg[1] = nullptr; rt.tile_row0[1] = nullptr;
-  rt.tile_m[0] = p->tile_m; rt.tile_m[1] = 0;
+  rt.tile_m[0] = p->tile_m[0]; rt.tile_m[1] = p->tile_m[1];
   rt.key_bits = bits_for(c.max_tenants);
 
   const size_t d = c.d_model, f = c.d_ff, es = p->esize;
@@ -523,9 +526,10 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
 
   // ---- residency of the first layer: hits first (so they cannot be chosen as victims)
   const uint64_t now = ++p->clock;
-  int n_mtiles = 0;
+  int n_mtiles[2] = {0, 0};
   for (int t : p->distinct) {
-    n_mtiles += (p->tok_count[t] + p->tile_m - 1) / p->tile_m;
+    n_mtiles[0] += (p->tok_count[t] + p->tile_m[0] - 1) / p->tile_m[0];
+    if (p->tile_m[1]) n_mtiles[1] += (p->tok_count[t] + p->tile_m[1] - 1) / p->tile_m[1];
     const int s = p->slot_of_tenant[t];
     if (s >= 0) p->slot_stamp[s] = now;
   }
@@ -612,7 +616,8 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
       g.resid_f32 = resid_f32; g.out_f32 = out_f32; g.C2 = C2;
       g.pool = p->d_pool; g.slot_stride = p->slot_stride;
       g.w_off = lay + p->tl[tw].off; g.b_off = lay + p->tl[tb].off;
-      g.n_out = n_out; g.k = k; g.epi = epi; g.which_tiles = 0; g.n_mtiles = n_mtiles;
+      g.n_out = n_out; g.k = k; g.epi = epi; g.n_mtiles_list[0] = n_mtiles[0]; g.n_mtiles_list[1] = n_mtiles[1];
+      g.which_tiles = 0; g.n_mtiles = n_mtiles[0];
       ProfSpan ps(p, HMI_KERNEL_GEMM);
       if (p->bf16) launch_gemm_bf16(g, rt, s); else launch_gemm_f32(g, rt, s);
     };
