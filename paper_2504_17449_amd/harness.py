@@ -33,7 +33,7 @@ def load_tenants(pool: Pool, wl: synth.Workload, tenants: Optional[Iterable[int]
 
     def gen(tl):
         t, l = tl
-        return t, l, [synth.to_storage_bytes(a, wl.dtype) for a in synth.tenant_tensors(wl, t, l)]
+        return t, l, synth.tenant_storage(wl, t, l)
 
     with ThreadPoolExecutor(workers) as ex:
         for t, l, tensors in ex.map(gen, todo):

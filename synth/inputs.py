@@ -3,8 +3,8 @@
 Every array is a pure function of ``(seed, what, tenant-or-request, layer, tensor)``:
 a tenant's weights or a request's hidden states can be regenerated alone, so a
 consumer never has to materialise a whole 1 000- or 10 000-tenant pool to look at
-the few tenants a batch touches.  Values are drawn in fp32 and rounded ONCE to the
-storage dtype (bf16 or fp32); every consumer starts from those rounded values.
+the few tenants a batch touches.  Values are fp32 draws rounded ONCE to the storage
+dtype (bf16 or fp32); every consumer starts from those rounded values.
 
 Nothing here computes any part of the layer: only random draws, shape tables and
 dtype packing.
@@ -13,6 +13,8 @@ from __future__ import annotations
 
 from dataclasses import dataclass, replace
 from typing import List, Tuple
+
+import threading
 
 import numpy as np
 
@@ -123,33 +125,89 @@ def storage_to_f64(raw: np.ndarray, dtype: str) -> np.ndarray:
 
 
 # ---------------------------------------------------------------- keyed draws
+#
+# Normal draws come from one seeded master sequence z[0..T) ~ iid N(0,1) per seed (numpy
+# SFC64, generated once per process).  A tensor is a contiguous window of it at an offset
+# hashed from (seed, tag, tenant-or-request, layer, tensor): every tensor is exactly iid
+# normal, any tensor can be regenerated alone, and a 50 GB pool costs a memcpy instead of
+# 25 G calls of a normal sampler.  Windows of different tensors may overlap (as shifted
+# copies); nothing in the method can tell.
 
-def _gen(seed: int, tag: int, a: int = 0, b: int = 0, c: int = 0) -> np.random.Generator:
-    key0 = (int(seed) << 8) | int(tag)
-    key1 = (int(a) << 24) | (int(b) << 8) | int(c)
-    return np.random.Generator(np.random.Philox(key=[key0, key1]))
+_MASTER_LEN = 1 << 24          # 16 Mi draws; the largest single tensor has 4 Mi elements
+_MASK64 = (1 << 64) - 1
+_master_cache: dict = {}
+_master_lock = threading.Lock()
+
+
+def _mix64(z: int) -> int:
+    z = (z + 0x9E3779B97F4A7C15) & _MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+    return z ^ (z >> 31)
+
+
+def _offset(seed: int, tag: int, a: int, b: int, c: int, n: int) -> int:
+    k = _mix64(seed ^ 0x5851F42D4C957F2D)
+    for v in (tag, a, b, c):
+        k = _mix64(k ^ int(v))
+    return k % (_MASTER_LEN - n)
+
+
+def _master(seed: int, dtype: str, scale: float):
+    """(fp32 storage-exact values, storage bytes) of scale * z rounded to ``dtype``."""
+    key = (seed, dtype, scale)
+    if key in _master_cache:
+        return _master_cache[key]
+    with _master_lock:
+        if key in _master_cache:
+            return _master_cache[key]
+        zkey = (seed, "z")
+        if zkey not in _master_cache:
+            g = np.random.Generator(np.random.SFC64(np.random.SeedSequence([0x484D49, seed])))
+            _master_cache[zkey] = g.standard_normal(_MASTER_LEN, dtype=np.float32)
+        v = round_to_storage(_master_cache[zkey] * np.float32(scale), dtype)
+        raw = to_storage_bytes(v, dtype)
+        v.setflags(write=False)
+        raw.setflags(write=False)
+        _master_cache[key] = (v, raw)
+        return _master_cache[key]
+
+
+def _gen(seed: int, tag: int, a: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[(int(seed) << 8) | int(tag), int(a)]))
+
+
+def _tensor(wl: Workload, tenant: int, layer: int, idx: int, shape, kind: str, raw: bool):
+    n = int(np.prod(shape))
+    off = _offset(wl.seed, _TAG_WEIGHT, tenant, layer, idx, n)
+    v32, vraw = _master(wl.seed, wl.dtype, 0.02)
+    if kind == "g":      # LayerNorm gain 1 + N(0, 0.02): small, recomputed and re-rounded
+        g32 = round_to_storage(np.float32(1.0) + v32[off:off + n], wl.dtype)
+        return (to_storage_bytes(g32, wl.dtype) if raw else g32).reshape(shape)
+    return (vraw if raw else v32)[off:off + n].reshape(shape)
 
 
 def tenant_tensors(wl: Workload, tenant: int, layer: int = 0) -> List[np.ndarray]:
     """All tensors of one (tenant, layer) in canonical order, fp32 arrays holding
     storage-exact values.  Weights, biases and LayerNorm shifts ~ N(0, 0.02);
     LayerNorm gains ~ 1 + N(0, 0.02)."""
-    out = []
-    for idx, (_, shape, kind) in enumerate(tensor_specs(wl)):
-        g = _gen(wl.seed, _TAG_WEIGHT, tenant, layer, idx)
-        a = g.standard_normal(int(np.prod(shape)), dtype=np.float32) * np.float32(0.02)
-        if kind == "g":
-            a = a + np.float32(1.0)
-        out.append(round_to_storage(a, wl.dtype).reshape(shape))
-    return out
+    return [_tensor(wl, tenant, layer, i, shape, kind, False)
+            for i, (_, shape, kind) in enumerate(tensor_specs(wl))]
+
+
+def tenant_storage(wl: Workload, tenant: int, layer: int = 0) -> List[np.ndarray]:
+    """Same tensors as tenant_tensors, as the arrays a device consumer reads (bf16 bit
+    patterns as uint16, or fp32).  Mostly zero-copy views of the master sequence."""
+    return [_tensor(wl, tenant, layer, i, shape, kind, True)
+            for i, (_, shape, kind) in enumerate(tensor_specs(wl))]
 
 
 def hidden_states(wl: Workload, request: int, seq_len: int, batch: int = 0) -> np.ndarray:
     """Hidden states entering the task layers for one request: [seq_len, d] ~ N(0, 1),
     storage-exact fp32.  Stands in for the PLOT-retrieved representations (Sec. 3.3.1)."""
-    g = _gen(wl.seed, _TAG_X, request, batch & 0xFFFF)
-    a = g.standard_normal(seq_len * wl.d_model, dtype=np.float32)
-    return round_to_storage(a, wl.dtype).reshape(seq_len, wl.d_model)
+    n = seq_len * wl.d_model
+    off = _offset(wl.seed, _TAG_X, request, batch, 0, n)
+    return _master(wl.seed, wl.dtype, 1.0)[0][off:off + n].reshape(seq_len, wl.d_model)
 
 
 def _popularity_cdf(wl: Workload) -> np.ndarray:

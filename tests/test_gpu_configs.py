@@ -1,0 +1,180 @@
+"""GPU parity at the target's full configuration sizes, in the launch configuration bench.py
+times, on requests the oracle computes one by one (requests are independent, so a subsample
+of requests is an exact check of those rows), plus the host-tier (swap-in / LRU) behaviour."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import hmi_oracle as O
+from tests.oracle_side import compare, oracle_forward, rows_of
+from tests.test_gpu_parity import check_route
+
+pytestmark = pytest.mark.gpu
+
+
+def pick_sample(ids, lens, n_multi=8, n_single=16):
+    """First and last request of the largest multi-request segments (the top tenant's among
+    them), some singleton tenants, and the shortest and the longest sequence."""
+    ids = np.asarray(ids)
+    uniq, counts = np.unique(ids, return_counts=True)
+    by_size = uniq[np.argsort(-counts, kind="stable")]
+    sample = set()
+    for t in by_size[:n_multi]:
+        members = np.flatnonzero(ids == t)
+        sample.update([int(members[0]), int(members[-1])])
+    singles = uniq[counts == 1]
+    for t in singles[:: max(1, len(singles) // n_single)][:n_single]:
+        sample.add(int(np.flatnonzero(ids == t)[0]))
+    sample.update([int(np.argmin(lens)), int(np.argmax(lens))])
+    return sorted(sample)
+
+
+def run_full(wl, sample_kw=None, tenants=None):
+    from paper_2504_17449_amd import harness
+    t0 = time.time()
+    ids, lens, x = harness.batch_to_device(wl)
+    N = int(lens.sum())
+    pool = harness.create_pool(wl, max_tokens=N)
+    try:
+        harness.load_tenants(pool, wl, tenants, workers=16)
+        torch.cuda.synchronize()
+        print(f"{wl.name}: R={len(ids)} N={N} G={len(set(ids.tolist()))} pool loaded in {time.time() - t0:.1f}s",
+              flush=True)
+        y = torch.empty_like(x)
+        pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
+        torch.cuda.synchronize()
+        check_route(pool, ids, lens)
+        y_gpu = harness.device_to_f64(y)
+    finally:
+        pool.close()
+    sample = pick_sample(ids, lens, **(sample_kw or {}))
+    t1 = time.time()
+    y_ref = oracle_forward(wl, ids, lens, sample)
+    max_abs, rel, ok = compare(y_gpu, y_ref, rows_of(lens, sample), wl.dtype)
+    print(f"  {len(sample)} sampled requests, oracle {time.time() - t1:.1f}s: max_abs={max_abs:.3e} "
+          f"rel_fro={rel:.3e} max|y_ref|={np.nanmax(np.abs(y_ref)):.2f}", flush=True)
+    assert ok, (max_abs, rel)
+    assert np.isfinite(y_gpu).all()
+
+
+def test_hbert_two_encoder_layers_1000_tenants_full_size():
+    run_full(synth.WORKLOADS["hbert_enc2"])
+
+
+def test_hgpt_decoder_layer_2000_tenants_ragged_full_size():
+    run_full(synth.WORKLOADS["hgpt_dec"], sample_kw=dict(n_multi=6, n_single=10))
+
+
+def test_adapter_block_1000_tenants_full_size():
+    run_full(synth.WORKLOADS["hbert_adapter"])
+
+
+# ------------------------------------------------------------------ host tier
+
+class LruModel:
+    """Host-side mirror of the documented cache policy: a slot's stamp is the clock of the
+    call that last used it; a miss takes a free slot, else evicts the slot with the oldest
+    stamp (ties: lowest tenant id), never a tenant of the batch being set up."""
+
+    def __init__(self, slots):
+        self.slots, self.stamp, self.clock = slots, {}, 0
+        self.hits = self.misses = self.evictions = 0
+
+    def batch(self, tenant_ids):
+        self.clock += 1
+        distinct = list(dict.fromkeys(int(t) for t in tenant_ids))
+        for t in distinct:
+            if t in self.stamp:
+                self.stamp[t] = self.clock
+        for t in distinct:
+            if t in self.stamp:
+                self.hits += 1
+                continue
+            self.misses += 1
+            if len(self.stamp) >= self.slots:
+                victim = min((s, v) for v, s in self.stamp.items() if s < self.clock)[1]
+                del self.stamp[victim]
+                self.evictions += 1
+            self.stamp[t] = self.clock
+
+
+@pytest.mark.parametrize("slots", [3, 6])
+def test_host_tier_tiny_cache_evicts_every_batch(slots):
+    """fp32, 12 tenants behind a 3- or 6-slot HBM cache: every batch swaps tenants in on the side
+    stream; outputs still match the oracle and the hit / miss / eviction counts are the LRU model's."""
+    from paper_2504_17449_amd import harness
+    wl = synth.Workload("tier_f32", synth.BLOCK_ENC_POSTLN, "f32", 64, 128, 4, 1, 12, 6, 3, 40,
+                        "uniform", 0.0, 1e-5, slots, True, seed=11)
+    pool = harness.create_pool(wl, max_requests=8, max_tokens=8 * 40)
+    model = LruModel(slots)
+    try:
+        harness.load_tenants(pool, wl)
+        for t in range(min(slots, wl.n_tenants)):       # load order fills the free slots
+            model.stamp[t] = 0
+        rng = np.random.default_rng(5)
+        for batch in range(8):
+            _, lens, x = harness.batch_to_device(wl, batch)
+            # at most `slots` distinct tenants per batch, drawn from all 12
+            ids = rng.choice(rng.permutation(wl.n_tenants)[:slots], size=wl.n_requests).astype(np.int32)
+            y = torch.empty_like(x)
+            pool.forward(0, x, y, ids, lens)
+            model.batch(ids)
+            torch.cuda.synchronize()
+            y_ref = oracle_forward(wl, ids, lens, batch=batch)
+            max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, np.arange(len(y_ref)), wl.dtype)
+            assert ok, (batch, max_abs, rel)
+        st = pool.stats()
+        assert (st["hits"], st["misses"], st["evictions"]) == (model.hits, model.misses, model.evictions)
+        assert st["misses"] > 0 and st["evictions"] > 0
+        assert st["bytes_h2d"] == st["misses"] * pool.image_bytes
+        # capacity error: more distinct tenants in one batch than slots, y untouched
+        ids = np.arange(slots + 1, dtype=np.int32)
+        lens = np.full(slots + 1, 3, np.int32)
+        x = torch.zeros(3 * (slots + 1), wl.d_model, device="cuda")
+        y = torch.full_like(x, 5.0)
+        import paper_2504_17449_amd as hmi
+        assert hmi.hmi_layer_forward(pool.h, 0, x.data_ptr(), y.data_ptr(), ids, lens) == hmi.HMI_ERR_CAPACITY
+        torch.cuda.synchronize()
+        assert bool((y == 5.0).all())
+    finally:
+        pool.close()
+
+
+def test_host_tier_zipf_batches_with_prefetch_bf16():
+    """The 10k-tenant recipe at reduced size: 1 500 tenants in pinned host memory behind a
+    160-slot HBM cache, Zipf 0.8 popularity, ragged lengths, two layers.  Batch b+1 is
+    prefetched while batch b computes; layer 1 is swapped in under layer 0 (Sec. 6.2)."""
+    from paper_2504_17449_amd import harness
+    wl = synth.WORKLOADS["hbert_10k"].scaled(name="hbert_tier_small", n_tenants=1500, hbm_slots=160,
+                                             n_requests=128, n_layers=2)
+    n_batches = 3
+    batches = [synth.batch_ids_lens(wl, b) for b in range(n_batches)]
+    touched = sorted(set(np.concatenate([b[0] for b in batches]).tolist()) | set(range(wl.hbm_slots)))
+    pool = harness.create_pool(wl, max_tokens=wl.n_requests * wl.seq_max)
+    try:
+        t0 = time.time()
+        harness.load_tenants(pool, wl, touched, workers=16)   # the lowest ids (the Zipf head) warm the cache
+        print(f"{wl.name}: {len(touched)} tenants x 2 layers in pinned memory, {time.time() - t0:.1f}s", flush=True)
+        outs = []
+        for b in range(n_batches):
+            ids, lens, x = harness.batch_to_device(wl, b)
+            y = torch.empty_like(x)
+            pool.stack_forward(0, 2, x, y, ids, lens)
+            if b + 1 < n_batches:
+                pool.prefetch(0, batches[b + 1][0])           # overlaps with this batch's kernels
+            outs.append((ids, lens, y))
+        torch.cuda.synchronize()
+        st = pool.stats()
+        print(f"  stats {st}", flush=True)
+        assert st["misses"] > 0 and st["evictions"] > 0
+        for b, (ids, lens, y) in enumerate(outs):
+            sample = pick_sample(ids, lens, n_multi=3, n_single=5)
+            y_ref = oracle_forward(wl, ids, lens, sample, batch=b)
+            max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, rows_of(lens, sample), wl.dtype)
+            print(f"  batch {b}: {len(sample)} requests max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+            assert ok, (b, max_abs, rel)
+    finally:
+        pool.close()
