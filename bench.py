@@ -45,7 +45,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_ffn")
-    ap.add_argument("--cpu-sample", type=int, default=64, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="requests the oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; collectives and sharding are not part of it "
