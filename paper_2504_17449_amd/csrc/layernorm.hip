@@ -76,11 +76,92 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a, Route rt) {
   }
 }
 
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 load4(const void* p, size_t idx, bool f32) {
+  if (f32) return *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(p) + idx);
+  const u16x4 h = *reinterpret_cast<const u16x4*>(reinterpret_cast<const uint16_t*>(p) + idx);
+  f32x4 v = {bf2f(h[0]), bf2f(h[1]), bf2f(h[2]), bf2f(h[3])};
+  return v;
+}
+
+// Vector path for d % 256 == 0: a lane owns d/256 pieces of 4 consecutive columns
+// (16-byte fp32 / 8-byte bf16 accesses, a wavefront covers 1 KB / 512 B contiguous).
+template <bool BF16, bool IN_F32, int NV>
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) {
+  const int lane = threadIdx.x & 63;
+  const int srow = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (srow >= a.n_rows) return;
+  int lo = 0, hi = rt.n_segments[0];
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (rt.seg_tok_off[mid] <= srow) lo = mid; else hi = mid;
+  }
+  const size_t slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
+  const size_t row = (size_t)rt.row_src[srow];
+  constexpr int nv = NV, d = NV * 256;
+  constexpr bool in_f32 = IN_F32 || !BF16;
+  f32x4 v[NV];
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    {
+      v[i] = load4(a.in, row * d + i * 256 + lane * 4, in_f32);
+      s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
+    }
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { const float c = v[i][e] - mean; q += c * c; }
+    }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + a.eps);
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    {
+      const int col = i * 256 + lane * 4;
+      const f32x4 gg = load4(a.pool + slot_base + a.g_off, col, !BF16);
+      const f32x4 bb = load4(a.pool + slot_base + a.b_off, col, !BF16);
+      f32x4 y;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) y[e] = (v[i][e] - mean) * rstd * gg[e] + bb[e];
+      const size_t idx = row * d + col;
+      if (a.out_f32) *reinterpret_cast<f32x4*>(a.out_f32 + idx) = y;
+      if (a.out_st) {
+        if (BF16) {
+          u16x4 h = {f2bf(y[0]), f2bf(y[1]), f2bf(y[2]), f2bf(y[3])};
+          *reinterpret_cast<u16x4*>(reinterpret_cast<uint16_t*>(a.out_st) + idx) = h;
+        } else {
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out_st) + idx) = y;
+        }
+      }
+    }
+}
+
 }  // namespace
+
+template <int NV>
+static void launch_vec(const LnArgs& a, const Route& rt, hipStream_t s, unsigned blocks) {
+  if (!a.bf16) hipLaunchKernelGGL((layernorm_vec_kernel<false, true, NV>), dim3(blocks), dim3(256), 0, s, a, rt);
+  else if (a.in_f32) hipLaunchKernelGGL((layernorm_vec_kernel<true, true, NV>), dim3(blocks), dim3(256), 0, s, a, rt);
+  else hipLaunchKernelGGL((layernorm_vec_kernel<true, false, NV>), dim3(blocks), dim3(256), 0, s, a, rt);
+}
 
 void launch_layernorm(const LnArgs& a, const Route& rt, hipStream_t s) {
   if (a.n_rows <= 0) return;
   const unsigned blocks = (unsigned)((a.n_rows + 3) / 4);
+  switch (a.d) {
+    case 256: return launch_vec<1>(a, rt, s, blocks);
+    case 512: return launch_vec<2>(a, rt, s, blocks);
+    case 768: return launch_vec<3>(a, rt, s, blocks);
+    case 1024: return launch_vec<4>(a, rt, s, blocks);
+    case 2048: return launch_vec<8>(a, rt, s, blocks);
+    default: break;
+  }
   if (a.bf16) hipLaunchKernelGGL(layernorm_kernel<true>, dim3(blocks), dim3(256), 0, s, a, rt);
   else hipLaunchKernelGGL(layernorm_kernel<false>, dim3(blocks), dim3(256), 0, s, a, rt);
 }
