@@ -444,7 +444,7 @@ void launch_gemm_bf16(const GemmArgs& g0, const Route& rt, hipStream_t s) {
   GemmArgs g = g0;
   static const int variant = getenv("HMI_GEMM_VARIANT") ? atoi(getenv("HMI_GEMM_VARIANT")) : 0;
   auto use_list = [&](int which) { g.which_tiles = which; g.n_mtiles = g.n_mtiles_list[which]; };
-  if (g.n_out % 256 == 0 && g.k % 64 == 0 && variant == 0) {
+  if (g.n_out % 256 == 0 && g.k % 64 == 0 && g.k >= 192 && variant == 0) {
     use_list(0); launch_gemm_bf16_p256(g, rt, s);
   } else if (g.n_out % 256 == 0 && g.k % 32 == 0 && variant == 4) {
     use_list(1); launch_gemm_bf16_t128(g, rt, s);

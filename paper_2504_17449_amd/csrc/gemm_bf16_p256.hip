@@ -1,30 +1,38 @@
-// Grouped bf16 GEMM, 256 x 256 tiles with 64-wide k-stages (the main kernel for wide layers).
+// Grouped bf16 GEMM, persistent workgroups, 256 x 256 tiles with 64-wide k-stages: the main
+// kernel for layers whose output width is a multiple of 256.
 //
 // Same contract as the other grouped GEMMs (one launch multiplies every tenant segment of a
 // mixed batch by that tenant's own weights, Sec. 6.3):
 //      C[rows, :] = epi( A[rows, :] * W_g^T + b_g )        for every m-tile of segment g
 //
-// What bounds this kernel on gfx950 is the number of requests the L2 serves, not the matrix
-// cores: an L2 channel answers one request per clock, 128 bytes if the request covers a full
-// cache line, 64 if it covers half of one (measured: 33 TB/s against 17-20 TB/s for
-// direct-to-LDS copies that hit in L2).  Hence
-//   * 256 x 256 tiles: the fewest operand bytes per FLOP that the register file allows
-//     (8 wavefronts x 128 accumulator registers);
-//   * k-stages of 64 bf16 = 128 bytes per row: eight lanes of a direct-to-LDS load fetch one
-//     whole cache line of a row, every request is a full line;
-//   * LDS (all 160 KB) is a ring of 2 activation stages and 3 weight stages of 32 KB: the
-//     weight stream, which mostly misses L2 (a weight panel is shared by the few m-tiles of
-//     one tenant), runs two stages ahead, the activation stream, which mostly hits (a panel
-//     is shared by all n-tiles), one stage ahead.  A wavefront issues its activation copies
-//     before its weight copies, so that with in-order completion waiting for "all but the
-//     newest weight stage" is exactly the condition for the next stage.
-//   * Operand roles are swapped (weights are the MFMA's first operand, in a permuted row
-//     order): a lane ends up with one row of C and 16 consecutive columns per MFMA tile, so
-//     the epilogue stores 32-byte (bf16) or 64-byte (fp32) runs straight from registers and
-//     the bias is folded into the accumulator initialisation.
-//   * 16-byte chunks are XOR-swizzled so that fragment reads are bank-conflict free for
-//     both row orders; workgroup ids are folded so that each XCD owns a contiguous range of
-//     tiles (neighbours share panels in that XCD's L2).
+// Measured facts about gfx950 that shape it
+//   * An L2 channel answers one request per clock: 128 bytes if the request covers a whole
+//     cache line, 64 if it covers half of one (33 TB/s against 17-20 TB/s for direct-to-LDS
+//     copies that hit in L2).  Stores follow the same rule: a wavefront store that touches
+//     64 different lines costs 64 requests however few bytes it carries.
+//   * The matrix pipe blocks a wavefront's instruction issue for half the duration of an
+//     MFMA; about four other instructions fit behind each one.
+//   * LDS reads run at 256 B/clk, fragment traffic is not a bound for 64 x 128 wavefront tiles.
+// Hence
+//   * 256 x 256 tiles (8 wavefronts x 128 accumulator registers): the fewest operand bytes
+//     per FLOP the register file allows;
+//   * k-stages of 64 bf16 = 128 bytes per row: the eight lanes that copy a row fetch one
+//     whole cache line, every operand request is a full line;
+//   * all 160 KB of LDS are a ring of 2 activation and 3 weight stages of 32 KB; weight
+//     copies (mostly L2 misses: a weight panel is shared only by the m-tiles of one
+//     tenant) run two stages ahead, activation copies (mostly hits) one.  A wavefront
+//     issues activation copies before weight copies, so with in-order completion "all but
+//     the newest weight stage have landed" is exactly the condition for the next stage;
+//   * one workgroup per compute unit walks over its share of the tiles.  Copies for the
+//     next tile are issued while the current one finishes, fragment reads are double
+//     buffered in registers one k-step ahead (across stage and tile boundaries), and there
+//     is one barrier per stage, placed so that the MFMAs of the last k-step hide it;
+//   * operand roles are swapped (weights are the MFMA's first operand, in a permuted row
+//     order): a lane ends up with one row of C and 16 consecutive columns per MFMA tile;
+//     bias is folded into the accumulator initialisation.  For the stores each wavefront
+//     transposes its results through the part of the two idle ring slots that only its
+//     own copies overwrite (no barrier), so that 16 or 32 consecutive lanes write one
+//     row's 256 or 512 contiguous bytes: full-line requests again.
 #include "hmi_kernels.h"
 
 namespace hmi {
@@ -34,16 +42,18 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kXcds = 8;
 constexpr int BM = 256, BN = 256, BK = 64, NW = 8, NTH = 64 * NW;
 constexpr int WTM = 64, WTN = 128, TM = 2, TN = 4;          // wavefront tile (4 x 2 wavefronts), MFMA tiles
 constexpr int ROW_BYTES = BK * 2;                            // 128: one cache line per row and stage
 constexpr int A_STAGES = 2, W_STAGES = 3;
-constexpr int A_STAGE_BYTES = BM * ROW_BYTES, W_STAGE_BYTES = BN * ROW_BYTES;   // 32 KB each
-constexpr int W_RING = A_STAGES * A_STAGE_BYTES;             // byte offset of the weight ring
-constexpr int LDS_BYTES = W_RING + W_STAGES * W_STAGE_BYTES; // 163840 = all of it
-constexpr int A_LD = BM / 8 / NW, B_LD = BN / 8 / NW;        // 1 KB (8 rows x 128 B) loads per wavefront and stage
+constexpr int STAGE_BYTES = BM * ROW_BYTES;                  // 32 KB, same for both operands
+constexpr int W_RING = A_STAGES * STAGE_BYTES;               // byte offset of the weight ring
+constexpr int LDS_BYTES = W_RING + W_STAGES * STAGE_BYTES;   // 163840 = all of it
+constexpr int LD = BM / 8 / NW;                              // 4 one-KB copies (8 rows x 128 B) per wavefront, operand and stage
+constexpr int WAVE_SLICE = LD * 1024;                        // the 4 KB of a stage slot that one wavefront's copies fill
 
 __device__ __forceinline__ float bf2f(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
@@ -80,261 +90,412 @@ __device__ __forceinline__ int swz_w(int row) { return ((row >> 1) & 3) | (((row
 __device__ __forceinline__ int perm_w(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 
 #define HMI_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+#define HMI_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
-struct Tile { int n0, row0, rows; size_t slot_base; };
+// What a lane needs to know about a tile: where its copies come from and where the bias is.
+struct TileRegs {
+  int n0, row0, rows;
+  const char* Wb;                  // first weight row of the tile: tenant's matrix + n0 rows
+  const uint16_t* bias;
+  uint32_t a_off[LD];              // byte offsets of this lane's activation copy sources at k = 0, plus 3072 - 1024 j
+  int out_row;                     // where row (wavefront's first row + lane) of the tile goes in C (row clamped to the tile)
+};
+
+__device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, int w, int wave, int lane, TileRegs& tr) {
+  const int nt_n = g.n_out / BN;
+  const int mt = w / nt_n;
+  tr.n0 = (w % nt_n) * BN;
+  const int seg = rt.tile_seg[g.which_tiles][mt];
+  tr.row0 = rt.tile_row0[g.which_tiles][mt];
+  tr.rows = min(BM, rt.seg_tok_off[seg + 1] - tr.row0);
+  const size_t slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
+  tr.Wb = g.pool + slot_base + g.w_off + (size_t)tr.n0 * (size_t)(g.k * 2);
+  tr.bias = reinterpret_cast<const uint16_t*>(g.pool + slot_base + g.b_off);
+  tr.out_row = rt.row_src[tr.row0 + min((wave >> 1) * WTM + lane, tr.rows - 1)];
+  // lane l fills LDS position (row l/8, chunk l%8) of an 8-row block with the global chunk
+  // position ^ swizzle(row): the eight lanes of a row cover its whole 128-byte line.
+#pragma unroll
+  for (int j = 0; j < LD; ++j) {
+    const int row = (wave * LD + j) * 8 + (lane >> 3);
+    const int src = rt.row_src[tr.row0 + min(row, tr.rows - 1)];
+    tr.a_off[j] = (uint32_t)src * (uint32_t)(g.lda * 2) + (((lane & 7) ^ swz_a(row)) << 4) + (3072 - j * 1024);
+  }
+}
 
 #ifdef HMI_EXP_CLOCK
 __device__ unsigned long long hmi_dbg_clk[4];
-__device__ unsigned long long hmi_dbg_wg[4096 * 4];
 #endif
-
-__device__ __forceinline__ bool locate(const GemmArgs& g, const Route& rt, Tile& tc) {
-  const int nt_n = g.n_out / BN;
-  const int total = g.n_mtiles * nt_n;
-  const int per = (total + kXcds - 1) / kXcds;
-  const int local = blockIdx.x / kXcds;
-  const int w = (blockIdx.x % kXcds) * per + local;
-  if (local >= per || w >= total) return false;
-  const int mt = w / nt_n;
-  tc.n0 = (w % nt_n) * BN;
-  const int seg = rt.tile_seg[g.which_tiles][mt];
-  tc.row0 = rt.tile_row0[g.which_tiles][mt];
-  tc.rows = min(BM, rt.seg_tok_off[seg + 1] - tc.row0);
-  tc.slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
-  return true;
-}
 
 template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
 __global__ __launch_bounds__(NTH) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void gemm_bf16_p256_kernel(GemmArgs g, Route rt) {
+void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-  Tile tc;
-  if (!locate(g, rt, tc)) return;
-#ifdef HMI_EXP_CLOCK
-  const unsigned long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
-#endif
-  const int rows = tc.rows, n0 = tc.n0;
-  const char* Wb = g.pool + tc.slot_base + g.w_off;
-  const uint16_t* bias = reinterpret_cast<const uint16_t*>(g.pool + tc.slot_base + g.b_off);
-  const char* Ab = reinterpret_cast<const char*>(g.A);
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int l32 = lane & 31, lh = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
-  const int K = g.k;
-  const int KT = K / BK;
+  const int KT = g.k / BK;
+  const char* Ab = reinterpret_cast<const char*>(g.A);
 
-  // ---- global sources of this lane's direct-to-LDS copies (byte offsets at k = 0): lane l
-  // fills LDS slot (row l/8, position l%8) of an 8-row block with global chunk
-  // position ^ swizzle(row); the eight lanes of a row cover its whole 128-byte line.
-  uint32_t a_off[A_LD], b_off[B_LD];
-#pragma unroll
-  for (int j = 0; j < A_LD; ++j) {
-    const int row = (wave * A_LD + j) * 8 + (lane >> 3);
-    const int src = rt.row_src[tc.row0 + min(row, rows - 1)];
-    a_off[j] = (uint32_t)src * (uint32_t)(g.lda * 2) + (((lane & 7) ^ swz_a(row)) << 4);
-  }
-#pragma unroll
-  for (int j = 0; j < B_LD; ++j) {
-    const int row = (wave * B_LD + j) * 8 + (lane >> 3);
-    b_off[j] = (uint32_t)(n0 + row) * (uint32_t)(K * 2) + (((lane & 7) ^ swz_w(row)) << 4);
-  }
+  // ---- this workgroup's tiles: XCD x (workgroups are dealt to XCDs round robin) owns the
+  // contiguous range [x per_xcd, (x+1) per_xcd), its workgroups take every n_local-th tile.
+  const int n_local = gridDim.x / kXcds;
+  const int w_end = min((int)(blockIdx.x % kXcds + 1) * per_xcd, total);
+  int w = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  if (w >= w_end) return;
+#ifdef HMI_EXP_CLOCK
+  const unsigned long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
+#endif
 
-  // Past the end both issue macros re-read the last stage (in bounds) into a ring slot that
-  // nobody reads any more, which keeps the outstanding-copy count uniform.
-#define HMI_ISSUE_A(S_IDX)                                                                        \
-  {                                                                                               \
-    const int s_ = (S_IDX);                                                                       \
-    const int kb_ = min(s_, KT - 1) * ROW_BYTES;                                                  \
-    unsigned char* base_ = smem + (s_ % A_STAGES) * A_STAGE_BYTES;                                \
-    _Pragma("unroll") for (int j = 0; j < A_LD; ++j)                                              \
-        __builtin_amdgcn_global_load_lds((glb_ptr_t)(Ab + kb_ + a_off[j]),                        \
-                                         (lds_ptr_t)(base_ + (wave * A_LD + j) * 1024), 16, 0, 0);\
-  }
-#define HMI_ISSUE_W(S_IDX)                                                                        \
-  {                                                                                               \
-    const int s_ = (S_IDX);                                                                       \
-    const int kb_ = min(s_, KT - 1) * ROW_BYTES;                                                  \
-    unsigned char* base_ = smem + W_RING + (s_ % W_STAGES) * W_STAGE_BYTES;                       \
-    _Pragma("unroll") for (int j = 0; j < B_LD; ++j)                                              \
-        __builtin_amdgcn_global_load_lds((glb_ptr_t)(Wb + kb_ + b_off[j]),                        \
-                                         (lds_ptr_t)(base_ + (wave * B_LD + j) * 1024), 16, 0, 0);\
+  TileRegs cur, nxt;
+  load_tile(g, rt, w, wave, lane, cur);
+  load_tile(g, rt, w + n_local < w_end ? w + n_local : w, wave, lane, nxt);
+
+  // weight copies: the lane part of the source offset (plus 3072 - 1024 j) is the same for every tile
+  uint32_t b_off[LD];
+#pragma unroll
+  for (int j = 0; j < LD; ++j) {
+    const int row = (wave * LD + j) * 8 + (lane >> 3);
+    b_off[j] = (uint32_t)row * (uint32_t)(g.k * 2) + (((lane & 7) ^ swz_w(row)) << 4) + (3072 - j * 1024);
   }
 
-  // ---- accumulators start at the bias: lane half h of MFMA tile j holds columns
-  // n0 + wn*128 + j*32 + 16 h + (0..15), the same for both m-tiles.
-  u32x4 bias_lo[TN], bias_hi[TN];
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col0 = n0 + wn * WTN + j * 32 + 16 * lh;
-    bias_lo[j] = *reinterpret_cast<const u32x4*>(bias + col0);
-    bias_hi[j] = *reinterpret_cast<const u32x4*>(bias + col0 + 8);
-  }
-  HMI_ISSUE_A(0)
-  HMI_ISSUE_W(0)
-  HMI_ISSUE_W(1)
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const u32x4 b0 = bias_lo[j], b1 = bias_hi[j];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      acc[0][j][2 * q] = bf2f(b0[q] & 0xffffu);      acc[0][j][2 * q + 1] = bf2f(b0[q] >> 16);
-      acc[0][j][8 + 2 * q] = bf2f(b1[q] & 0xffffu);  acc[0][j][8 + 2 * q + 1] = bf2f(b1[q] >> 16);
-    }
-#pragma unroll
-    for (int i = 1; i < TM; ++i) acc[i][j] = acc[0][j];
-  }
-
-  // ---- fragment read offsets inside a stage for the four k-steps of a stage
-  int fx_off[4], fw_off[4];
+  // ---- fragment read offsets inside a stage slot for the four k-steps of a stage
+  // (k-step ks reads chunk (2 ks + lh) ^ swizzle: that is the k-step 0 offset with ks << 5 XORed in)
+  int fx_base, fw_base;
   {
     const int rx = wm * WTM + l32;                       // + 32 i: swizzle unchanged
     const int rw = wn * WTN + perm_w(l32);               // + 32 j: swizzle unchanged
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      fx_off[ks] = rx * ROW_BYTES + (((ks * 2 + lh) ^ swz_a(rx)) << 4);
-      fw_off[ks] = W_RING + rw * ROW_BYTES + (((ks * 2 + lh) ^ swz_w(rw)) << 4);
-    }
+    fx_base = rx * ROW_BYTES + ((lh ^ swz_a(rx)) << 4);
+    fw_base = W_RING + rw * ROW_BYTES + ((lh ^ swz_w(rw)) << 4);
   }
 
-  const bool wave_active = wm * WTM < rows;
-
-  for (int s = 0; s < KT; ++s) {
-    HMI_WAIT_VMCNT(B_LD);                                // all but the newest weight stage have landed
-    __builtin_amdgcn_s_barrier();                        // ... everybody's, and stage s-1 is no longer read
-    __builtin_amdgcn_sched_barrier(0);
-    HMI_ISSUE_A(s + 1)
-    HMI_ISSUE_W(s + 2)
-    if (wave_active) {
-      const unsigned char* xa = smem + (s % A_STAGES) * A_STAGE_BYTES;
-      const unsigned char* wa = smem + (s % W_STAGES) * W_STAGE_BYTES;
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 fx[TM], fw[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fx[i] = *reinterpret_cast<const bf16x8*>(xa + fx_off[ks] + i * 32 * ROW_BYTES);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fw[j] = *reinterpret_cast<const bf16x8*>(wa + fw_off[ks] + j * 32 * ROW_BYTES);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-#ifndef HMI_EXP_NO_MFMA
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[j], fx[i], acc[i][j], 0, 0, 0);
-#else
-            { acc[i][j][0] += (float)fw[j][0] + (float)fx[i][0]; }
+  // Ring bookkeeping (uniform): a_rd / w_rd are the byte offsets of the slots that hold the
+  // stage being multiplied.  Activation stage s+2 and weight stage s+3 are copied into exactly
+  // those slots once stage s is done, so no separate fill position is needed; a stage index
+  // of KT or more means a stage of the next tile (for the last tile: an in-bounds re-read
+  // of its own first stages that nobody consumes).  Needs KT >= 3, so that the copies
+  // never reach the tile after next.
+  int a_rd = 0, w_rd = 0;
+#ifdef HMI_EXP_NO_FRAG
+  bool exp_first = true;
 #endif
+  // The four 1 KB copies of a wavefront's slice share one LDS base (one M0 write); the
+  // instruction offset j KB that separates them applies to the global address too, so
+  // the lane offsets carry 3072 - j KB and the uniform base pointer -3072.
+#define HMI_COPY4(SRC, VOFF, SLOT_OFF)                                                            \
+  {                                                                                               \
+    const char* src_ = (SRC) - 3072;                                                              \
+    lds_ptr_t dst_ = (lds_ptr_t)(smem + (SLOT_OFF) + wave * WAVE_SLICE);                          \
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[0]), dst_, 16, 0, 0);              \
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[1]), dst_, 16, 1024, 0);           \
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[2]), dst_, 16, 2048, 0);           \
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[3]), dst_, 16, 3072, 0);           \
+  }
+  static_assert(LD == 4, "HMI_COPY4 issues four copies");
+
+  bf16x8 fx[2][TM], fw[2][TN];
+  f32x16 acc[TM][TN];
+
+  // loads the MFMA fragments of k-step KS of the stage in slots a_rd / w_rd into register buffer B
+#ifdef HMI_EXP_NO_FRAG
+#define HMI_READ_FRAGS(B, KS) { if (exp_first) { HMI_READ_FRAGS_REAL(0, KS) HMI_READ_FRAGS_REAL(1, KS) exp_first = false; } }
+#else
+#define HMI_READ_FRAGS(B, KS) HMI_READ_FRAGS_REAL(B, KS)
+#endif
+#define HMI_READ_FRAGS_REAL(B, KS)                                                                \
+  {                                                                                               \
+    const unsigned char* xa_ = smem + a_rd + (fx_base ^ ((KS) << 5));                             \
+    const unsigned char* wa_ = smem + w_rd + (fw_base ^ ((KS) << 5));                             \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) fx[B][i] = *reinterpret_cast<const bf16x8*>(xa_ + i * 32 * ROW_BYTES); \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j) fw[B][j] = *reinterpret_cast<const bf16x8*>(wa_ + j * 32 * ROW_BYTES); \
+  }
+#ifndef HMI_EXP_NO_MFMA
+#define HMI_MFMAS(B)                                                                              \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                  \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][j], fx[B][i], acc[i][j], 0, 0, 0);
+#else
+#define HMI_MFMAS(B)                                                                              \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                  \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                \
+      acc[i][j][0] += (float)fw[B][j][0] + (float)fx[B][i][0];
+#endif
+
+  // scheduling: each of the 6 fragment reads of the next k-step goes behind one MFMA of
+  // this k-step (the wait for this k-step's fragments then comes before any new read)
+#define HMI_SCHED_READS_THEN_MFMAS()                                                              \
+  _Pragma("unroll") for (int z_ = 0; z_ < TM + TN; ++z_) {                                        \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                            \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                            \
+  }                                                                                               \
+  __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - TM - TN, 0);                              \
+  __builtin_amdgcn_sched_barrier(0);
+
+  // accumulators of a tile start at its bias: lane half h of MFMA tile j holds columns
+  // n0 + wn*128 + j*32 + 16 h + (0..15), the same for both m-tiles.
+#define HMI_INIT_ACC(TR)                                                                          \
+  _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                                \
+    const int col0_ = (TR).n0 + wn * WTN + j * 32 + 16 * lh;                                      \
+    const u32x4 b0_ = *reinterpret_cast<const u32x4*>((TR).bias + col0_);                         \
+    const u32x4 b1_ = *reinterpret_cast<const u32x4*>((TR).bias + col0_ + 8);                     \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                               \
+      acc[0][j][2 * q] = bf2f(b0_[q] & 0xffffu);      acc[0][j][2 * q + 1] = bf2f(b0_[q] >> 16);  \
+      acc[0][j][8 + 2 * q] = bf2f(b1_[q] & 0xffffu);  acc[0][j][8 + 2 * q + 1] = bf2f(b1_[q] >> 16); \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = 1; i < TM; ++i) acc[i][j] = acc[0][j];                         \
+  }
+
+  // One stage.  MODE says where the copies issued after the barrier come from:
+  //   0: activation stage s+2 and weight stage s+3 of the current tile
+  //   1: (s = KT-3) activation stage KT-1 of the current tile, weight stage 0 of the next
+  //   2: (s = KT-2) activation stage 0 and weight stage 1 of the next tile
+  //   3: (s = KT-1) none: the freed slots serve the epilogue first
+#ifdef HMI_EXP_NO_COPY
+#define HMI_STAGE_COPIES(MODE) { (void)fa_; (void)fw_; }
+#else
+#define HMI_STAGE_COPIES(MODE)                                                                    \
+  {                                                                                               \
+    if (MODE == 0) { HMI_COPY4(Ab + (s + 2) * ROW_BYTES, cur.a_off, fa_) HMI_COPY4(cur.Wb + (s + 3) * ROW_BYTES, b_off, W_RING + fw_) } \
+    if (MODE == 1) { HMI_COPY4(Ab + (s + 2) * ROW_BYTES, cur.a_off, fa_) HMI_COPY4(nxt.Wb, b_off, W_RING + fw_) }                     \
+    if (MODE == 2) { HMI_COPY4(Ab, nxt.a_off, fa_) HMI_COPY4(nxt.Wb + ROW_BYTES, b_off, W_RING + fw_) }                                \
+  }
+#endif
+#define HMI_ITER(MODE)                                                                            \
+  {                                                                                               \
+    if (wave_active) {                                                                            \
+      HMI_READ_FRAGS(1, 1)                                                                        \
+      HMI_MFMAS(0)                                                                                \
+      HMI_SCHED_READS_THEN_MFMAS()                                                                \
+      HMI_READ_FRAGS(0, 2)                                                                        \
+      HMI_MFMAS(1)                                                                                \
+      HMI_SCHED_READS_THEN_MFMAS()                                                                \
+      HMI_READ_FRAGS(1, 3)                                                                        \
+      HMI_MFMAS(0)                                                                                \
+      HMI_SCHED_READS_THEN_MFMAS()                                                                \
+    }                                                                                             \
+    HMI_WAIT_LGKMCNT0();          /* this wavefront no longer reads stage s from LDS */           \
+    HMI_WAIT_VMCNT(LD);           /* its copies of stage s+1 (both operands) have landed */       \
+    __builtin_amdgcn_s_barrier(); /* ... everybody's, and nobody reads stage s any more */        \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    const int fa_ = a_rd, fw_ = w_rd;                                                             \
+    a_rd ^= STAGE_BYTES;                                                                          \
+    w_rd = w_rd == (W_STAGES - 1) * STAGE_BYTES ? 0 : w_rd + STAGE_BYTES;                         \
+    if (MODE == 3) {                                                                              \
+      patch_a = fa_; patch_w = fw_;                                                               \
+      if (wm * WTM < nxt.rows) HMI_READ_FRAGS(0, 0)                                               \
+      __builtin_amdgcn_sched_barrier(0);                                                          \
+      if (wave_active) { HMI_MFMAS(1) }                                                           \
+    } else if (wave_active) {                                                                     \
+      /* first fragments of stage s+1, then the last k-step's MFMAs with the copies between them */ \
+      HMI_READ_FRAGS(0, 0)                                                                        \
+      HMI_STAGE_COPIES(MODE)                                                                      \
+      HMI_MFMAS(1)                                                                                \
+      __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);                                    \
+      _Pragma("unroll") for (int z_ = 0; z_ < 2 * LD; ++z_) {                                     \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                        \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                        \
+      }                                                                                           \
+    } else {                                                                                      \
+      HMI_STAGE_COPIES(MODE)                                                                      \
+    }                                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+  }
+
+  // ---- prologue of the first tile.  Issue order W(0) A(0) W(1) A(1) W(2) is the steady
+  // state's order, so the same "all but the newest weight stage" wait works from the start.
+  HMI_INIT_ACC(cur)
+  HMI_COPY4(cur.Wb, b_off, W_RING)
+  HMI_COPY4(Ab, cur.a_off, 0)
+  HMI_COPY4(cur.Wb + ROW_BYTES, b_off, W_RING + STAGE_BYTES)
+  HMI_COPY4(Ab + ROW_BYTES, cur.a_off, STAGE_BYTES)
+  HMI_COPY4(cur.Wb + 2 * ROW_BYTES, b_off, W_RING + 2 * STAGE_BYTES)
+  HMI_WAIT_VMCNT(3 * LD);
+  __builtin_amdgcn_s_barrier();
+  bool wave_active = wm * WTM < cur.rows;
+  if (wave_active) HMI_READ_FRAGS(0, 0)
+  int patch_a = 0, patch_w = 0;
+
+  for (;;) {
+    // ================= main loop of the current tile =================
+    {
+      int s = 0;
+      for (; s < KT - 3; ++s) HMI_ITER(0)
+      HMI_ITER(1)
+      HMI_ITER(2)
+      HMI_ITER(3)
+    }
+
+#ifdef HMI_EXP_CLOCK
+    const unsigned long long dbg_e0 = wall_clock64();
+#endif
+#ifndef HMI_EXP_NO_EPI
+    // ================= epilogue of the current tile =================
+    // Staging patch of this wavefront: its own 4 KB slice of the two slots that stage KT-1
+    // occupied.  A row keeps its 16-byte chunk c at chunk position c ^ (row & 15).
+    // Rows past the end of a short tile are replaced by the tile's last row of the same
+    // 32-row block (same data to the same address: harmless), which keeps the code free
+    // of branches so that the loads and stores of a pass are issued back to back.
+    if (wave_active) {
+      unsigned char* patch0 = smem + patch_a + wave * WAVE_SLICE;
+      unsigned char* patch1 = smem + W_RING + patch_w + wave * WAVE_SLICE;
+      // The 8 KB patch holds 32 rows of 256 bytes (rows 0-15 in patch0, 16-31 in patch1): all
+      // 128 columns of an MFMA tile row as bf16, or 64 of them as fp32 (two passes).  After
+      // the transposition 16 lanes hold one row's 256 contiguous bytes, 4 rows per step.
+      // Results that get a residual added cross the patch in fp32 even if they are stored as
+      // bf16, so that they are rounded once, after the addition.
+      constexpr bool STAGE_F32 = OUT_F32 || EPI == EPI_BIAS_RESID;
+      constexpr int PASSES = STAGE_F32 ? 2 : 1;
+      constexpr int COLS_PER_CHUNK = STAGE_F32 ? 4 : 8;
+      const int c = lane & 15;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int mbase = wm * WTM + i * 32;
+        if (mbase < cur.rows) {
+          const int rmax = min(31, cur.rows - 1 - mbase);     // last valid row of this 32-row block
+          unsigned char* wrow = ((l32 & 16) ? patch1 : patch0) + (l32 & 15) * 256;
+          uint32_t orow[8];                                   // row of C for each of this lane's 8 pieces
+#pragma unroll
+          for (int it = 0; it < 8; ++it) orow[it] = (uint32_t)__shfl(cur.out_row, i * 32 + min(it * 4 + (lane >> 4), rmax), 64);
+#pragma unroll
+          for (int pass = 0; pass < PASSES; ++pass) {
+            const int col = cur.n0 + wn * WTN + pass * 64 + c * COLS_PER_CHUNK;
+            // residuals first, so that they arrive while the results cross the patch
+            f32x4 rv32[(EPI == EPI_BIAS_RESID && RESID_F32) ? 8 : 1];
+            u32x2 rv16[(EPI == EPI_BIAS_RESID && !RESID_F32) ? 8 : 1];
+            if (EPI == EPI_BIAS_RESID) {
+#pragma unroll
+              for (int it = 0; it < 8; ++it) {
+                if (RESID_F32) rv32[it] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g.resid) + (size_t)orow[it] * g.ldr + col);
+                else rv16[it] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(g.resid) + (size_t)orow[it] * g.ldr + col);
+              }
+            }
+            // accumulator layout -> patch
+            if (STAGE_F32) {
+#pragma unroll
+              for (int jj = 0; jj < 2; ++jj) {
+                const int j = pass * 2 + jj;
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                  f32x4 o = {acc[i][j][4 * qd], acc[i][j][4 * qd + 1], acc[i][j][4 * qd + 2], acc[i][j][4 * qd + 3]};
+                  if (EPI == EPI_BIAS_GELU) { o[0] = gelu_poly(o[0]); o[1] = gelu_poly(o[1]); o[2] = gelu_poly(o[2]); o[3] = gelu_poly(o[3]); }
+                  else if (EPI == EPI_BIAS_RELU) { o[0] = fmaxf(o[0], 0.f); o[1] = fmaxf(o[1], 0.f); o[2] = fmaxf(o[2], 0.f); o[3] = fmaxf(o[3], 0.f); }
+                  const int c0 = jj * 8 + lh * 4 + qd;
+                  *reinterpret_cast<f32x4*>(wrow + ((c0 ^ (l32 & 15)) << 4)) = o;
+                }
+              }
+            } else {
+#pragma unroll
+              for (int j = 0; j < TN; ++j) {
+                float v[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                  v[r] = acc[i][j][r];
+                  if (EPI == EPI_BIAS_GELU) v[r] = gelu_poly(v[r]);
+                  else if (EPI == EPI_BIAS_RELU) v[r] = fmaxf(v[r], 0.0f);
+                }
+                u32x4 h0, h1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { h0[e] = pack_bf16(v[2 * e], v[2 * e + 1]); h1[e] = pack_bf16(v[8 + 2 * e], v[8 + 2 * e + 1]); }
+                const int c0 = j * 4 + lh * 2;
+                *reinterpret_cast<u32x4*>(wrow + ((c0 ^ (l32 & 15)) << 4)) = h0;
+                *reinterpret_cast<u32x4*>(wrow + (((c0 + 1) ^ (l32 & 15)) << 4)) = h1;
+              }
+            }
+            HMI_WAIT_LGKMCNT0();
+            // patch -> rows of C
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+              const int r = min(it * 4 + (lane >> 4), rmax);
+              const unsigned char* rrow = ((r & 16) ? patch1 : patch0) + (r & 15) * 256;
+              const size_t off = (size_t)orow[it] * g.ldc + col;
+              if (STAGE_F32) {
+                f32x4 v = *reinterpret_cast<const f32x4*>(rrow + ((c ^ (r & 15)) << 4));
+                if (EPI == EPI_BIAS_RESID) {
+                  if (RESID_F32) v += rv32[it];
+                  else {
+                    v[0] += bf2f(rv16[it][0] & 0xffffu); v[1] += bf2f(rv16[it][0] >> 16);
+                    v[2] += bf2f(rv16[it][1] & 0xffffu); v[3] += bf2f(rv16[it][1] >> 16);
+                  }
+                }
+                const u32x2 hh = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                if (OUT_F32) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + off) = v;
+                else *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C) + off) = hh;
+                if (HAS_C2) *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C2) + off) = hh;
+              } else {
+                const u32x4 h = *reinterpret_cast<const u32x4*>(rrow + ((c ^ (r & 15)) << 4));
+                *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C) + off) = h;
+                if (HAS_C2) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C2) + off) = h;
+              }
+            }
+          }
+        }
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-#undef HMI_ISSUE_A
-#undef HMI_ISSUE_W
-  HMI_WAIT_VMCNT(0);   // the tail copies (re-reads of the last stage) must not outlive the workgroup
+#else
+    // (experiment: keep the accumulators alive without an epilogue)
+    { float sacc = 0.f;
+      for (int i = 0; i < TM; ++i) for (int j = 0; j < TN; ++j) for (int r = 0; r < 16; ++r) sacc += acc[i][j][r];
+      if (sacc == 12345.678f) reinterpret_cast<float*>(g.C)[0] = sacc; }
+#endif
+
 #ifdef HMI_EXP_CLOCK
-  if (threadIdx.x == 0 && blockIdx.x < 4096) {
-    unsigned hwid, xcc;
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-    hmi_dbg_wg[blockIdx.x * 4 + 0] = dbg_w0; hmi_dbg_wg[blockIdx.x * 4 + 1] = wall_clock64();
-    hmi_dbg_wg[blockIdx.x * 4 + 2] = ((unsigned long long)xcc << 32) | hwid; hmi_dbg_wg[blockIdx.x * 4 + 3] = (unsigned long long)tc.rows;
+    if (threadIdx.x == 0) atomicAdd(&hmi_dbg_clk[3], wall_clock64() - dbg_e0);
+#endif
+    // ================= move on to the next tile =================
+    w += n_local;
+    if (w >= w_end) break;
+    cur = nxt;
+    wave_active = wm * WTM < cur.rows;
+    HMI_INIT_ACC(cur)
+    // the copies that were held back at the last stage (the new tile's activation stage 1
+    // and weight stage 2) go into the slots the epilogue just used; a wavefront's copies
+    // fill only its own slice of a slot, which is its own staging patch: no barrier
+    HMI_COPY4(Ab + ROW_BYTES, cur.a_off, patch_a)
+    HMI_COPY4(cur.Wb + 2 * ROW_BYTES, b_off, W_RING + patch_w)
+    load_tile(g, rt, w + n_local < w_end ? w + n_local : w, wave, lane, nxt);
   }
+  HMI_WAIT_VMCNT(0);   // none of this workgroup's copies may outlive it
+#ifdef HMI_EXP_CLOCK
   if (threadIdx.x == 0) {
     atomicAdd(&hmi_dbg_clk[0], clock64() - dbg_c0); atomicAdd(&hmi_dbg_clk[1], wall_clock64() - dbg_w0); atomicAdd(&hmi_dbg_clk[2], 1ull);
   }
 #endif
-  if (!wave_active) return;
-#ifdef HMI_EXP_NO_EPI
-  { float sacc = 0.f;
-    for (int i = 0; i < TM; ++i) for (int j = 0; j < TN; ++j) for (int r = 0; r < 16; ++r) sacc += acc[i][j][r];
-    if (sacc == 12345.678f) reinterpret_cast<float*>(g.C)[0] = sacc;
-    return; }
-#endif
-
-  // ---- epilogue straight from the accumulators: lane = row, 16 consecutive columns per tile
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = wm * WTM + i * 32 + l32;
-    if (m >= rows) continue;
-    const size_t orow = (size_t)rt.row_src[tc.row0 + m];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col0 = n0 + wn * WTN + j * 32 + 16 * lh;
-      float v[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        v[r] = acc[i][j][r];
-        if (EPI == EPI_BIAS_GELU) v[r] = gelu_poly(v[r]);
-        else if (EPI == EPI_BIAS_RELU) v[r] = fmaxf(v[r], 0.0f);
-      }
-      if (EPI == EPI_BIAS_RESID) {
-        if (RESID_F32) {
-          const f32x4* rp = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g.resid) + orow * g.ldr + col0);
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const f32x4 rv = rp[q];
-            v[4 * q] += rv[0]; v[4 * q + 1] += rv[1]; v[4 * q + 2] += rv[2]; v[4 * q + 3] += rv[3];
-          }
-        } else {
-          const u32x4* rp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(g.resid) + orow * g.ldr + col0);
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const u32x4 rv = rp[q];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { v[8 * q + 2 * e] += bf2f(rv[e] & 0xffffu); v[8 * q + 2 * e + 1] += bf2f(rv[e] >> 16); }
-          }
-        }
-      }
-      u32x4 h0, h1;
-      if (!OUT_F32 || HAS_C2) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { h0[e] = pack_bf16(v[2 * e], v[2 * e + 1]); h1[e] = pack_bf16(v[8 + 2 * e], v[8 + 2 * e + 1]); }
-      }
-      if (OUT_F32) {
-        f32x4* cp = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + orow * g.ldc + col0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { f32x4 o = {v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]}; cp[q] = o; }
-      } else {
-        u32x4* cp = reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C) + orow * g.ldc + col0);
-        cp[0] = h0; cp[1] = h1;
-      }
-      if (HAS_C2) {
-        u32x4* cp = reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C2) + orow * g.ldc + col0);
-        cp[0] = h0; cp[1] = h1;
-      }
-    }
-  }
 }
 
 template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
 void launch_one(const GemmArgs& g, const Route& rt, hipStream_t s) {
   static bool attr_set = false;
+  static int n_cu = 0;
   auto kern = gemm_bf16_p256_kernel<EPI, OUT_F32, RESID_F32, HAS_C2>;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     attr_set = true;
   }
+  if (n_cu == 0) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < kXcds) n_cu = 256;
+  }
   const int nt_n = g.n_out / BN;
   const long long total = (long long)g.n_mtiles * nt_n;
   if (total <= 0) return;
-  const int per = (int)((total + kXcds - 1) / kXcds);
-  hipLaunchKernelGGL(kern, dim3(per * kXcds), dim3(NTH), LDS_BYTES, s, g, rt);
+  const int per_xcd = (int)((total + kXcds - 1) / kXcds);
+  const int local = per_xcd < n_cu / kXcds ? per_xcd : n_cu / kXcds;   // workgroups per XCD: at most one per compute unit
+  hipLaunchKernelGGL(kern, dim3(local * kXcds), dim3(NTH), LDS_BYTES, s, g, rt, (int)total, per_xcd);
 }
 
 }  // namespace
 
 #ifdef HMI_EXP_CLOCK
 void dbg_clock_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(hmi_dbg_clk), 32); }
-void dbg_wg_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(hmi_dbg_wg), 4096 * 32); }
+void dbg_wg_read(unsigned long long* out) { for (int i = 0; i < 4096 * 4; ++i) out[i] = 0; }
 #endif
 
-// Preconditions (checked by the caller): n_out % 256 == 0, k % 64 == 0, k >= 64,
+// Preconditions (checked by the caller): n_out % 256 == 0, k % 64 == 0, k >= 192,
 // which_tiles names a list of 256-row m-tiles, all operands 16-byte aligned,
 // byte offsets of A rows and of W rows inside a slot below 4 GB.
 void launch_gemm_bf16_p256(const GemmArgs& g, const Route& rt, hipStream_t s) {
