@@ -26,8 +26,9 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_F32_TFLOPS = 157.3     # fp32 vector
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (scaled by a copy kernel of known size); filled in from profiles/ once measured.
-MEASURED_TRAFFIC_BYTES = {}
+# (scaled by a copy kernel of known size in the same run, see --copy-calibration):
+# mean over the FFN1 and FFN2 launches, from profiles/gemm_bf16_p256_bert_ffn.md.
+MEASURED_TRAFFIC_BYTES = {"bert_ffn": 8.05e8}
 
 
 def linear_flops_per_token(wl) -> float:
@@ -46,6 +47,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_ffn")
     ap.add_argument("--cpu-sample", type=int, default=256, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run one plain device copy of this many MiB (a kernel of known HBM traffic that "
+                         "scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the same run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; collectives and sharding are not part of it "
@@ -123,6 +127,14 @@ def main() -> int:
         cpu = {"value": round(toks / dt, 1), "unit": "tokens/s per layer", "cores": int(cores), "kind": "oracle",
                "sample": f"first {len(sample)} of {len(ids)} requests ({int(lens[sample].sum())} tokens x "
                          f"{wl.n_layers} layers), numpy fp64, {dt:.1f} s incl. regenerating their weights"}
+
+    if args.copy_calibration > 0:
+        src = torch.ones(args.copy_calibration << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # one elementwise copy kernel: reads and writes copy_calibration MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     stats = pool.stats()
     pool.close()

@@ -80,6 +80,27 @@ __device__ __forceinline__ float gelu_poly(float x) {
   return fmaf(-a, q, fmaxf(x, 0.0f));
 }
 
+// The same GELU on two values at once in packed fp16 arithmetic, for results that are stored
+// as bf16 anyway (fp16 carries 11 significant bits against the 8 of the result: the rms error
+// of the rounded result grows by about 3 %).  12 packed operations and 4 conversions per pair.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t gelu_pair_to_bf16(float x0, float x1) {
+  const f16x2 x = {(_Float16)x0, (_Float16)x1};
+  const f16x2 zero = {(_Float16)0.0f, (_Float16)0.0f};
+  auto k = [](float v) { f16x2 r = {(_Float16)v, (_Float16)v}; return r; };
+  const f16x2 a = __builtin_elementwise_min(__builtin_elementwise_abs(x), k(4.0f));
+  const f16x2 u = __builtin_elementwise_fma(a, k(0.5f), k(-1.0f));
+  f16x2 q = k(-0.0411399369f);
+  q = __builtin_elementwise_fma(q, u, k(0.0706263031f));
+  q = __builtin_elementwise_fma(q, u, k(0.0492447267f));
+  q = __builtin_elementwise_fma(q, u, k(-0.212425632f));
+  q = __builtin_elementwise_fma(q, u, k(0.219460411f));
+  q = __builtin_elementwise_fma(q, u, k(-0.108456779f));
+  q = __builtin_elementwise_fma(q, u, k(0.0226731103f));
+  const f16x2 y = __builtin_elementwise_fma(-a, q, __builtin_elementwise_max(x, zero));
+  return pack_bf16((float)y[0], (float)y[1]);
+}
+
 // LDS chunk swizzles (a row is 8 chunks of 16 bytes, two rows per 256-byte bank line).
 // Activation rows are read by consecutive lanes in consecutive order; weight rows in the
 // permuted order perm_w.  Either way the 16 lanes served together hit 16 distinct chunks.
@@ -105,12 +126,19 @@ struct TileRegs {
 };
 
 __device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, int w, int wave, int lane, TileRegs& tr) {
+  // Tile order: segment by segment; inside a segment n-tile by n-tile with the segment's
+  // m-tiles innermost, so that the tiles which share a weight panel (and the few that
+  // share an activation panel) run next to each other and the panel is fetched from HBM once.
   const int nt_n = g.n_out / BN;
-  const int mt = w / nt_n;
-  tr.n0 = (w % nt_n) * BN;
-  const int seg = rt.tile_seg[g.which_tiles][mt];
-  tr.row0 = rt.tile_row0[g.which_tiles][mt];
-  tr.rows = min(BM, rt.seg_tok_off[seg + 1] - tr.row0);
+  const int mt_any = w / nt_n;                               // some m-tile of the segment w falls in
+  const int seg = rt.tile_seg[g.which_tiles][mt_any];
+  const int s0 = rt.seg_tok_off[seg], s1 = rt.seg_tok_off[seg + 1];
+  const int mt_first = mt_any - (rt.tile_row0[g.which_tiles][mt_any] - s0) / BM;
+  const int mt_cnt = (s1 - s0 + BM - 1) / BM;
+  const int q = w - mt_first * nt_n;
+  tr.n0 = (q / mt_cnt) * BN;
+  tr.row0 = s0 + (q % mt_cnt) * BM;
+  tr.rows = min(BM, s1 - tr.row0);
   const size_t slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
   tr.Wb = g.pool + slot_base + g.w_off + (size_t)tr.n0 * (size_t)(g.k * 2);
   tr.bias = reinterpret_cast<const uint16_t*>(g.pool + slot_base + g.b_off);
@@ -390,16 +418,17 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
             } else {
 #pragma unroll
               for (int j = 0; j < TN; ++j) {
-                float v[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                  v[r] = acc[i][j][r];
-                  if (EPI == EPI_BIAS_GELU) v[r] = gelu_poly(v[r]);
-                  else if (EPI == EPI_BIAS_RELU) v[r] = fmaxf(v[r], 0.0f);
-                }
                 u32x4 h0, h1;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { h0[e] = pack_bf16(v[2 * e], v[2 * e + 1]); h1[e] = pack_bf16(v[8 + 2 * e], v[8 + 2 * e + 1]); }
+                for (int e = 0; e < 4; ++e) {
+                  float v0 = acc[i][j][2 * e], v1 = acc[i][j][2 * e + 1], v2 = acc[i][j][8 + 2 * e], v3 = acc[i][j][8 + 2 * e + 1];
+                  if (EPI == EPI_BIAS_GELU) {
+                    h0[e] = gelu_pair_to_bf16(v0, v1); h1[e] = gelu_pair_to_bf16(v2, v3);
+                  } else {
+                    if (EPI == EPI_BIAS_RELU) { v0 = fmaxf(v0, 0.0f); v1 = fmaxf(v1, 0.0f); v2 = fmaxf(v2, 0.0f); v3 = fmaxf(v3, 0.0f); }
+                    h0[e] = pack_bf16(v0, v1); h1[e] = pack_bf16(v2, v3);
+                  }
+                }
                 const int c0 = j * 4 + lh * 2;
                 *reinterpret_cast<u32x4*>(wrow + ((c0 ^ (l32 & 15)) << 4)) = h0;
                 *reinterpret_cast<u32x4*>(wrow + (((c0 + 1) ^ (l32 & 15)) << 4)) = h1;
