@@ -1,4 +1,7 @@
-// Grouped bf16 GEMM on the gfx950 matrix cores with fused epilogues.
+// Grouped bf16 GEMM on the gfx950 matrix cores with fused epilogues: the dispatcher and the
+// two kernels for the shapes the persistent 256 x 256 kernel (gemm_bf16_p256.hip) does not
+// take: a short or odd k (k < 192 or k % 64 != 0) and output widths that are not a multiple
+// of 256 (adapter ranks, small test shapes).
 //
 // Computes, for every m-tile the router emitted (all rows of a tile belong to one tenant
 // segment g):   C[rows, :] = epi( A[rows, :] * W_g^T + b_g )
@@ -22,8 +25,6 @@
 //     s_barrier per stage, vmcnt-counted so that three stages stay in flight.
 //   * staged kernel (any n_out): global -> registers -> LDS, two 64-wide k-stages.
 #include "hmi_kernels.h"
-
-#include <cstdlib>
 
 namespace hmi {
 namespace {
@@ -442,21 +443,12 @@ void launch_dma(const GemmArgs& g, const Route& rt, hipStream_t s) {
 
 void launch_gemm_bf16(const GemmArgs& g0, const Route& rt, hipStream_t s) {
   GemmArgs g = g0;
-  static const int variant = getenv("HMI_GEMM_VARIANT") ? atoi(getenv("HMI_GEMM_VARIANT")) : 0;
-  auto use_list = [&](int which) { g.which_tiles = which; g.n_mtiles = g.n_mtiles_list[which]; };
-  if (g.n_out % 256 == 0 && g.k % 64 == 0 && g.k >= 192 && variant == 0) {
-    use_list(0); launch_gemm_bf16_p256(g, rt, s);
-  } else if (g.n_out % 256 == 0 && g.k % 32 == 0 && variant == 4) {
-    use_list(1); launch_gemm_bf16_t128(g, rt, s);
-  } else if (g.n_out % 256 == 0) {
-    if (variant == 1) { use_list(1); launch_dma<128, 256, 2, 2, 3>(g, rt, s); }
-    else if (variant == 2) { use_list(0); launch_dma<256, 256, 4, 2, 3>(g, rt, s); }
-    else { use_list(0); launch_dma<256, 256, 4, 2, 4>(g, rt, s); }
-  } else if (g.n_out % 128 == 0) {
-    use_list(0); launch_staged<256, 128, 4, 2>(g, rt, s);
-  } else {
-    use_list(0); launch_staged<256, 64, 8, 1>(g, rt, s);
-  }
+  g.which_tiles = 0;                       // all three kernels work on the list of 256-row m-tiles
+  g.n_mtiles = g.n_mtiles_list[0];
+  if (g.n_out % 256 == 0 && g.k % 64 == 0 && g.k >= 192) launch_gemm_bf16_p256(g, rt, s);
+  else if (g.n_out % 256 == 0) launch_dma<256, 256, 4, 2, 4>(g, rt, s);
+  else if (g.n_out % 128 == 0) launch_staged<256, 128, 4, 2>(g, rt, s);
+  else launch_staged<256, 64, 8, 1>(g, rt, s);
 }
 
 }  // namespace hmi

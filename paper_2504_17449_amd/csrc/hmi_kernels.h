@@ -60,10 +60,8 @@ struct GemmArgs {
 
 void launch_gemm_bf16(const GemmArgs& g, const Route& rt, hipStream_t s);
 void launch_gemm_f32(const GemmArgs& g, const Route& rt, hipStream_t s);
-// 128 x 256 tiles, two workgroups per compute unit; needs n_out % 256 == 0, k % 32 == 0 and
-// which_tiles / n_mtiles naming a list of 128-row m-tiles.
-void launch_gemm_bf16_t128(const GemmArgs& g, const Route& rt, hipStream_t s);
-// 256 x 256 tiles, 64-wide k-stages; needs n_out % 256 == 0, k % 64 == 0 and a list of 256-row m-tiles.
+// Persistent 256 x 256 tiles, 64-wide k-stages; needs n_out % 256 == 0, k % 64 == 0, k >= 192 and
+// which_tiles / n_mtiles naming the list of 256-row m-tiles.
 void launch_gemm_bf16_p256(const GemmArgs& g, const Route& rt, hipStream_t s);
 constexpr int kBf16TileM0 = 256, kBf16TileM1 = 128;  // heights of the two m-tile lists of bf16 pools
 constexpr int kF32TileM = 64;

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) 
   }
   const size_t slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
   const size_t row = (size_t)rt.row_src[srow];
-  constexpr int nv = NV, d = NV * 256;
+  constexpr int d = NV * 256;
   constexpr bool in_f32 = IN_F32 || !BF16;
   f32x4 v[NV];
   float s = 0.0f;
