@@ -157,6 +157,17 @@ __device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, in
 __device__ unsigned long long hmi_dbg_clk[4];
 #endif
 
+// The last workgroup of an XCD to finish puts the XCD's counters back to zero for the next launch.
+__device__ __forceinline__ void finish_workgroup(const Route& rt, int xcd, int n_local) {
+  if (threadIdx.x == 0) {
+    int* done = rt.gemm_sched + 8 + xcd;
+    if (atomicAdd(done, 1) == n_local - 1) {
+      __hip_atomic_store(rt.gemm_sched + xcd, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
 __global__ __launch_bounds__(NTH) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
@@ -170,18 +181,31 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   const char* Ab = reinterpret_cast<const char*>(g.A);
 
   // ---- this workgroup's tiles: XCD x (workgroups are dealt to XCDs round robin) owns the
-  // contiguous range [x per_xcd, (x+1) per_xcd), its workgroups take every n_local-th tile.
+  // contiguous range [x per_xcd, (x+1) per_xcd).  A workgroup's first two tiles are fixed
+  // (its index inside the XCD, plus one round); from the third on it claims the next
+  // unclaimed tile of the range, so that workgroups that drew cheap (short) tiles take more.
+  // Wavefront 0 claims the tile after next at the start of a tile and passes the answer to
+  // the other wavefronts through a mailbox in global memory (LDS has no byte to spare).
   const int n_local = gridDim.x / kXcds;
-  const int w_end = min((int)(blockIdx.x % kXcds + 1) * per_xcd, total);
-  int w = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  if (w >= w_end) return;
+  const int xcd = blockIdx.x % kXcds;
+  const int w_base = xcd * per_xcd;
+  const int w_end = min(w_base + per_xcd, total);
+  int* const claim_ctr = rt.gemm_sched + xcd;
+  int* const mailbox = rt.gemm_sched + 16 + blockIdx.x;
+  int w = w_base + blockIdx.x / kXcds;
+  int w_next = w + n_local;
+  if (w >= w_end) { finish_workgroup(rt, xcd, n_local); return; }
+  const bool claimer = wave == 0 && lane == 0;
+  int claimed = 0, mail = 0;
+  if (claimer) claimed = atomicAdd(claim_ctr, 1);
+  int budget = per_xcd;           // no workgroup can own more tiles than its XCD has: bounds the loop whatever the claims say
 #ifdef HMI_EXP_CLOCK
   const unsigned long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
 #endif
 
   TileRegs cur, nxt;
   load_tile(g, rt, w, wave, lane, cur);
-  load_tile(g, rt, w + n_local < w_end ? w + n_local : w, wave, lane, nxt);
+  load_tile(g, rt, w_next < w_end ? w_next : w, wave, lane, nxt);
 
   // weight copies: the lane part of the source offset (plus 3072 - 1024 j) is the same for every tile
   uint32_t b_off[LD];
@@ -306,9 +330,12 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
       HMI_SCHED_READS_THEN_MFMAS()                                                                \
     }                                                                                             \
     HMI_WAIT_LGKMCNT0();          /* this wavefront no longer reads stage s from LDS */           \
-    HMI_WAIT_VMCNT(LD);           /* its copies of stage s+1 (both operands) have landed */       \
+    if (MODE == 2 && wave == 0) { HMI_WAIT_VMCNT(0); }   /* ... and its mailbox store is done */   \
+    else { HMI_WAIT_VMCNT(LD); }  /* its copies of stage s+1 (both operands) have landed */       \
     __builtin_amdgcn_s_barrier(); /* ... everybody's, and nobody reads stage s any more */        \
     __builtin_amdgcn_sched_barrier(0);                                                            \
+    if (MODE == 1 && claimer) __hip_atomic_store(mailbox, claimed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); \
+    if (MODE == 2) mail = __hip_atomic_load(mailbox, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  \
     const int fa_ = a_rd, fw_ = w_rd;                                                             \
     a_rd ^= STAGE_BYTES;                                                                          \
     w_rd = w_rd == (W_STAGES - 1) * STAGE_BYTES ? 0 : w_rd + STAGE_BYTES;                         \
@@ -475,8 +502,10 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
     if (threadIdx.x == 0) atomicAdd(&hmi_dbg_clk[3], wall_clock64() - dbg_e0);
 #endif
     // ================= move on to the next tile =================
-    w += n_local;
-    if (w >= w_end) break;
+    w = w_next;
+    if (w >= w_end || --budget <= 0) break;
+    w_next = w_base + 2 * n_local + __builtin_amdgcn_readfirstlane(mail);
+    if (claimer) claimed = atomicAdd(claim_ctr, 1);
     cur = nxt;
     wave_active = wm * WTM < cur.rows;
     HMI_INIT_ACC(cur)
@@ -485,9 +514,10 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
     // fill only its own slice of a slot, which is its own staging patch: no barrier
     HMI_COPY4(Ab + ROW_BYTES, cur.a_off, patch_a)
     HMI_COPY4(cur.Wb + 2 * ROW_BYTES, b_off, W_RING + patch_w)
-    load_tile(g, rt, w + n_local < w_end ? w + n_local : w, wave, lane, nxt);
+    load_tile(g, rt, w_next < w_end ? w_next : w, wave, lane, nxt);
   }
   HMI_WAIT_VMCNT(0);   // none of this workgroup's copies may outlive it
+  finish_workgroup(rt, xcd, n_local);
 #ifdef HMI_EXP_CLOCK
   if (threadIdx.x == 0) {
     atomicAdd(&hmi_dbg_clk[0], clock64() - dbg_c0); atomicAdd(&hmi_dbg_clk[1], wall_clock64() - dbg_w0); atomicAdd(&hmi_dbg_clk[2], 1ull);

@@ -28,7 +28,11 @@ struct Route {
   int32_t* n_tiles[2];        // [1]
   int32_t tile_m[2];          // tile heights (0 = list unused)
   int32_t key_bits;           // bits needed for the largest tenant id (radix passes = bits/4)
+  // scratch of the persistent GEMM: per XCD a tile-claim counter [0..7] and a count of finished
+  // workgroups [8..15], then one mailbox per workgroup; all zero between launches
+  int32_t* gemm_sched;
 };
+constexpr int kGemmSchedInts = 16 + 1024;
 
 void launch_router(const Route& rt, int R, hipStream_t s);
 

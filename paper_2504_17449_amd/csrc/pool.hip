@@ -352,7 +352,8 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
                  + 2 * (size_t)Rm          // seg_tenant, seg_slot
                  + 2 * ((size_t)Rm + 1)    // seg_req_off, seg_tok_off
                  + MT                      // row_src
-                 + 2 * (max_tiles0 + max_tiles1) + 4;  // tile lists + counters
+                 + 2 * (max_tiles0 + max_tiles1) + 4   // tile lists + counters
+                 + kGemmSchedInts;
   CREATE_TRY(hipMalloc(&p->d_idx, n_i32 * sizeof(int32_t)));
   CREATE_TRY(hipMemset(p->d_idx, 0, n_i32 * sizeof(int32_t)));
   int32_t* q = p->d_idx;
@@ -367,6 +368,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   rt.tile_seg[1] = max_tiles1 ? take(max_tiles1) : nullptr;
   rt.tile_row0[1] = max_tiles1 ? take(max_tiles1) : nullptr;
   rt.n_segments = take(1); rt.n_tiles[0] = take(1); rt.n_tiles[1] = take(1);
+  rt.gemm_sched = take(kGemmSchedInts);
   rt.tile_m[0] = p->tile_m[0]; rt.tile_m[1] = p->tile_m[1];
   rt.key_bits = bits_for(c.max_tenants);
 
