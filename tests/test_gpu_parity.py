@@ -85,6 +85,26 @@ def test_layer_stack_in_one_call(hmi, block, dtype):
     run_case(hmi, small(block, dtype, n_layers=3, seq_max=140, **kw))
 
 
+@pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN])
+def test_wide_bf16_blocks_ragged_every_row(hmi, block):
+    """Widths that are multiples of 256 with k >= 192 take the persistent 256 x 256 GEMM: ragged
+    segments of 1..300 rows (short tiles, clamped rows, several tiles per segment), every output
+    row compared.  d = 256 makes k = 256 (4 stages), f = 512 makes k = 512 and two n-tiles."""
+    run_case(hmi, small(block, "bf16", d_model=256, d_ff=512, n_heads=4, n_requests=28, n_tenants=7,
+                        hbm_slots=7, n_layers=2 if block == synth.BLOCK_FFN else 1))
+
+
+def test_persistent_gemm_more_tiles_than_workgroups(hmi):
+    """Hundreds of one-request tenants: ~1700 tiles for 256 workgroups, so every workgroup claims
+    tiles at run time beyond its two fixed ones; k = 192 is the shortest reduction the kernel takes."""
+    wl = small(synth.BLOCK_FFN, "bf16", d_model=192, d_ff=1024, n_requests=640, n_tenants=900,
+               hbm_slots=900, seq_min=1, seq_max=9, popularity="uniform")
+    run_case(hmi, wl)
+    # the counters reset themselves: a second forward on a fresh pool object of another shape works as well
+    run_case(hmi, small(synth.BLOCK_FFN, "bf16", d_model=256, d_ff=768, n_requests=300, n_tenants=300,
+                        hbm_slots=300, seq_min=1, seq_max=5, popularity="uniform"), batch=1)
+
+
 def test_second_layer_alone(hmi):
     """forward(layer=1) uses layer 1's weights: equals the oracle fed layer-1 weights only."""
     from paper_2504_17449_amd import harness
