@@ -47,6 +47,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_ffn")
     ap.add_argument("--cpu-sample", type=int, default=256, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--tenants", type=int, default=0, help="override the workload's tenant count (host-tier runs at reduced size)")
+    ap.add_argument("--slots", type=int, default=0, help="override the number of HBM slots")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (a kernel of known HBM traffic that "
                          "scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the same run)")
@@ -64,30 +66,61 @@ def main() -> int:
     from paper_2504_17449_amd import harness
 
     wl = synth.WORKLOADS[args.workload]
+    if args.tenants or args.slots:
+        wl = wl.scaled(name=wl.name + "_scaled", n_tenants=args.tenants or wl.n_tenants,
+                       hbm_slots=args.slots or wl.hbm_slots)
     torch.cuda.set_device(0)
     t0 = time.time()
     ids, lens, x = harness.batch_to_device(wl)
     N = int(lens.sum())
     pool = harness.create_pool(wl, max_tokens=N)
-    harness.load_tenants(pool, wl)
+    harness.load_tenants(pool, wl, workers=16)
     y = torch.empty_like(x)
     print(f"[bench] {wl.name}: R={len(ids)} N={N} tenants={wl.n_tenants} distinct={len(set(ids.tolist()))} "
           f"image={pool.image_bytes / 1e6:.2f} MB setup={time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
+    # A pool with a host tier sees a different batch of tenant ids every step (same lengths and
+    # hidden states, so N is fixed), and the next batch's tenants are prefetched on the copy
+    # stream while the current batch computes (the paper's coarse pipelining, Sec. 6.2).
+    n_batches = args.warmup + 3 * args.steps + 1
+    batches = [ids] if not wl.host_tier else [synth.batch_ids_lens(wl, b)[0] for b in range(n_batches)]
+    counter = [0]
+
     def step():
-        pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
+        b = counter[0]
+        counter[0] += 1
+        if wl.host_tier:
+            cur = batches[b % len(batches)]
+            nxt = batches[(b + 1) % len(batches)]
+            pool.stack_forward(0, wl.n_layers, x, y, cur, lens)
+            for layer in range(wl.n_layers):
+                pool.prefetch(layer, np.unique(nxt))
+        else:
+            pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    stats0 = pool.stats()
     t1 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t1
+    stats1 = pool.stats()
     ms_per_step = elapsed * 1e3 / args.steps
     ms_per_layer = ms_per_step / wl.n_layers
     tokens_per_s = N / (ms_per_layer * 1e-3)
+
+    # ---- spread of the step time: the same steps once more with an event after each
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    step_ev[0].record()
+    for i in range(args.steps):
+        step()
+        step_ev[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(args.steps))
+    pct = lambda q: round(per_step[min(len(per_step) - 1, int(q * len(per_step)))], 5)
 
     # ---- dominant kernel: same steps again with HIP events around every kernel launch
     pool.profile(True)
@@ -147,9 +180,16 @@ def main() -> int:
         "config": {"workload": f"{wl.name}: {wl.n_tenants} tenants, {len(ids)} requests, {N} tokens, "
                                f"d={wl.d_model} f={wl.d_ff} heads={wl.n_heads} layers={wl.n_layers}",
                    "block": wl.block, "tenant_popularity": wl.popularity, "distinct_tenants": len(set(ids.tolist()))},
+        "ms_per_step_p10_p50_p90": [pct(0.10), pct(0.50), pct(0.90)],
         "step_tflops": round(flops_step / (ms_per_step * 1e-3) / 1e12, 2),
         "step_frac_of_peak": round(flops_step / (ms_per_step * 1e-3) / 1e12 / peak, 4),
         "pool": stats,
+        "host_tier": None if not wl.host_tier else {
+            "batches": "a new batch of tenant ids every step, next batch prefetched during the current one",
+            "hit_rate": round((stats1["hits"] - stats0["hits"]) /
+                              max(1, stats1["hits"] - stats0["hits"] + stats1["misses"] - stats0["misses"]), 4),
+            "h2d_GB_per_s": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / elapsed / 1e9, 2),
+            "h2d_MB_per_step": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / args.steps / 1e6, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
