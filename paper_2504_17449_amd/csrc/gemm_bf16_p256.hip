@@ -153,9 +153,6 @@ __device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, in
   }
 }
 
-#ifdef HMI_EXP_CLOCK
-__device__ unsigned long long hmi_dbg_clk[4];
-#endif
 
 // The last workgroup of an XCD to finish puts the XCD's counters back to zero for the next launch.
 __device__ __forceinline__ void finish_workgroup(const Route& rt, int xcd, int n_local) {
@@ -199,9 +196,6 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   int claimed = 0, mail = 0;
   if (claimer) claimed = atomicAdd(claim_ctr, 1);
   int budget = per_xcd;           // no workgroup can own more tiles than its XCD has: bounds the loop whatever the claims say
-#ifdef HMI_EXP_CLOCK
-  const unsigned long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
-#endif
 
   TileRegs cur, nxt;
   load_tile(g, rt, w, wave, lane, cur);
@@ -232,9 +226,6 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   // of its own first stages that nobody consumes).  Needs KT >= 3, so that the copies
   // never reach the tile after next.
   int a_rd = 0, w_rd = 0;
-#ifdef HMI_EXP_NO_FRAG
-  bool exp_first = true;
-#endif
   // The four 1 KB copies of a wavefront's slice share one LDS base (one M0 write); the
   // instruction offset j KB that separates them applies to the global address too, so
   // the lane offsets carry 3072 - j KB and the uniform base pointer -3072.
@@ -253,29 +244,17 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   f32x16 acc[TM][TN];
 
   // loads the MFMA fragments of k-step KS of the stage in slots a_rd / w_rd into register buffer B
-#ifdef HMI_EXP_NO_FRAG
-#define HMI_READ_FRAGS(B, KS) { if (exp_first) { HMI_READ_FRAGS_REAL(0, KS) HMI_READ_FRAGS_REAL(1, KS) exp_first = false; } }
-#else
-#define HMI_READ_FRAGS(B, KS) HMI_READ_FRAGS_REAL(B, KS)
-#endif
-#define HMI_READ_FRAGS_REAL(B, KS)                                                                \
+#define HMI_READ_FRAGS(B, KS)                                                                     \
   {                                                                                               \
     const unsigned char* xa_ = smem + a_rd + (fx_base ^ ((KS) << 5));                             \
     const unsigned char* wa_ = smem + w_rd + (fw_base ^ ((KS) << 5));                             \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) fx[B][i] = *reinterpret_cast<const bf16x8*>(xa_ + i * 32 * ROW_BYTES); \
     _Pragma("unroll") for (int j = 0; j < TN; ++j) fw[B][j] = *reinterpret_cast<const bf16x8*>(wa_ + j * 32 * ROW_BYTES); \
   }
-#ifndef HMI_EXP_NO_MFMA
 #define HMI_MFMAS(B)                                                                              \
   _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                  \
     _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                \
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][j], fx[B][i], acc[i][j], 0, 0, 0);
-#else
-#define HMI_MFMAS(B)                                                                              \
-  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                  \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                \
-      acc[i][j][0] += (float)fw[B][j][0] + (float)fx[B][i][0];
-#endif
 
   // scheduling: each of the 6 fragment reads of the next k-step goes behind one MFMA of
   // this k-step (the wait for this k-step's fragments then comes before any new read)
@@ -306,16 +285,12 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   //   1: (s = KT-3) activation stage KT-1 of the current tile, weight stage 0 of the next
   //   2: (s = KT-2) activation stage 0 and weight stage 1 of the next tile
   //   3: (s = KT-1) none: the freed slots serve the epilogue first
-#ifdef HMI_EXP_NO_COPY
-#define HMI_STAGE_COPIES(MODE) { (void)fa_; (void)fw_; }
-#else
 #define HMI_STAGE_COPIES(MODE)                                                                    \
   {                                                                                               \
     if (MODE == 0) { HMI_COPY4(Ab + (s + 2) * ROW_BYTES, cur.a_off, fa_) HMI_COPY4(cur.Wb + (s + 3) * ROW_BYTES, b_off, W_RING + fw_) } \
     if (MODE == 1) { HMI_COPY4(Ab + (s + 2) * ROW_BYTES, cur.a_off, fa_) HMI_COPY4(nxt.Wb, b_off, W_RING + fw_) }                     \
     if (MODE == 2) { HMI_COPY4(Ab, nxt.a_off, fa_) HMI_COPY4(nxt.Wb + ROW_BYTES, b_off, W_RING + fw_) }                                \
   }
-#endif
 #define HMI_ITER(MODE)                                                                            \
   {                                                                                               \
     if (wave_active) {                                                                            \
@@ -384,10 +359,6 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
       HMI_ITER(3)
     }
 
-#ifdef HMI_EXP_CLOCK
-    const unsigned long long dbg_e0 = wall_clock64();
-#endif
-#ifndef HMI_EXP_NO_EPI
     // ================= epilogue of the current tile =================
     // Staging patch of this wavefront: its own 4 KB slice of the two slots that stage KT-1
     // occupied.  A row keeps its 16-byte chunk c at chunk position c ^ (row & 15).
@@ -491,16 +462,7 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
         }
       }
     }
-#else
-    // (experiment: keep the accumulators alive without an epilogue)
-    { float sacc = 0.f;
-      for (int i = 0; i < TM; ++i) for (int j = 0; j < TN; ++j) for (int r = 0; r < 16; ++r) sacc += acc[i][j][r];
-      if (sacc == 12345.678f) reinterpret_cast<float*>(g.C)[0] = sacc; }
-#endif
 
-#ifdef HMI_EXP_CLOCK
-    if (threadIdx.x == 0) atomicAdd(&hmi_dbg_clk[3], wall_clock64() - dbg_e0);
-#endif
     // ================= move on to the next tile =================
     w = w_next;
     if (w >= w_end || --budget <= 0) break;
@@ -518,11 +480,6 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   }
   HMI_WAIT_VMCNT(0);   // none of this workgroup's copies may outlive it
   finish_workgroup(rt, xcd, n_local);
-#ifdef HMI_EXP_CLOCK
-  if (threadIdx.x == 0) {
-    atomicAdd(&hmi_dbg_clk[0], clock64() - dbg_c0); atomicAdd(&hmi_dbg_clk[1], wall_clock64() - dbg_w0); atomicAdd(&hmi_dbg_clk[2], 1ull);
-  }
-#endif
 }
 
 template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
@@ -549,10 +506,6 @@ void launch_one(const GemmArgs& g, const Route& rt, hipStream_t s) {
 
 }  // namespace
 
-#ifdef HMI_EXP_CLOCK
-void dbg_clock_read(unsigned long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(hmi_dbg_clk), 32); }
-void dbg_wg_read(unsigned long long* out) { for (int i = 0; i < 4096 * 4; ++i) out[i] = 0; }
-#endif
 
 // Preconditions (checked by the caller): n_out % 256 == 0, k % 64 == 0, k >= 192,
 // which_tiles names a list of 256-row m-tiles, all operands 16-byte aligned,
