@@ -119,26 +119,41 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, f32x16 (&acc)[TM][TN
         patch[((r >> 2) * 8 + lh * 4 + (r & 3)) * PITCH + j * 32 + l32] = v;
       }
     __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wavefront's LDS writes are done
-    // LDS patch -> global, 16-byte row pieces
+    // LDS patch -> global, 16-byte row pieces.  Rows past the end of a short tile are replaced
+    // by the block's last valid row (same value to the same address: harmless), so that there
+    // is no branch per piece and the residual loads of a batch are issued back to back,
+    // ahead of the stores.
+    if (gcol < g.n_out) {
+      const int rmax = min(31, rows - 1 - mbase);
+      constexpr int BATCH = ITS < 8 ? ITS : 8;
 #pragma unroll
-    for (int it = 0; it < ITS; ++it) {
-      const int lr = it * ROWS_PER_IT + rrow, m = mbase + lr;
-      if (m < rows && gcol < g.n_out) {
-        f32x4 v = *reinterpret_cast<const f32x4*>(patch + lr * PITCH + rcol);
-        const size_t orow = (size_t)rowsrc_s[m];
-        if (epi == EPI_BIAS_RESID) {
-          if (g.resid_f32) {
-            v += *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g.resid) + orow * g.ldr + gcol);
-          } else {
-            const u16x4 rv = *reinterpret_cast<const u16x4*>(reinterpret_cast<const uint16_t*>(g.resid) + orow * g.ldr + gcol);
-            v[0] += bf2f(rv[0]); v[1] += bf2f(rv[1]); v[2] += bf2f(rv[2]); v[3] += bf2f(rv[3]);
+      for (int it0 = 0; it0 < ITS; it0 += BATCH) {
+        size_t orow[BATCH];
+        f32x4 rv32[BATCH];
+        u16x4 rv16[BATCH];
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+          const int lr = min((it0 + b) * ROWS_PER_IT + rrow, rmax);
+          orow[b] = (size_t)rowsrc_s[mbase + lr];
+          if (epi == EPI_BIAS_RESID) {
+            if (g.resid_f32) rv32[b] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(g.resid) + orow[b] * g.ldr + gcol);
+            else rv16[b] = *reinterpret_cast<const u16x4*>(reinterpret_cast<const uint16_t*>(g.resid) + orow[b] * g.ldr + gcol);
           }
         }
-        u16x4 h;
-        h[0] = f2bf(v[0]); h[1] = f2bf(v[1]); h[2] = f2bf(v[2]); h[3] = f2bf(v[3]);
-        if (g.out_f32) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + orow * g.ldc + gcol) = v;
-        else *reinterpret_cast<u16x4*>(reinterpret_cast<uint16_t*>(g.C) + orow * g.ldc + gcol) = h;
-        if (g.C2) *reinterpret_cast<u16x4*>(reinterpret_cast<uint16_t*>(g.C2) + orow * g.ldc + gcol) = h;
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b) {
+          const int lr = min((it0 + b) * ROWS_PER_IT + rrow, rmax);
+          f32x4 v = *reinterpret_cast<const f32x4*>(patch + lr * PITCH + rcol);
+          if (epi == EPI_BIAS_RESID) {
+            if (g.resid_f32) v += rv32[b];
+            else { v[0] += bf2f(rv16[b][0]); v[1] += bf2f(rv16[b][1]); v[2] += bf2f(rv16[b][2]); v[3] += bf2f(rv16[b][3]); }
+          }
+          u16x4 h;
+          h[0] = f2bf(v[0]); h[1] = f2bf(v[1]); h[2] = f2bf(v[2]); h[3] = f2bf(v[3]);
+          if (g.out_f32) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + orow[b] * g.ldc + gcol) = v;
+          else *reinterpret_cast<u16x4*>(reinterpret_cast<uint16_t*>(g.C) + orow[b] * g.ldc + gcol) = h;
+          if (g.C2) *reinterpret_cast<u16x4*>(reinterpret_cast<uint16_t*>(g.C2) + orow[b] * g.ldc + gcol) = h;
+        }
       }
     }
     __builtin_amdgcn_s_waitcnt(0xC07F);   // reads done before the patch is overwritten

@@ -91,26 +91,31 @@ __device__ __forceinline__ f32x4 load4(const void* p, size_t idx, bool f32) {
 // (16-byte fp32 / 8-byte bf16 accesses, a wavefront covers 1 KB / 512 B contiguous).
 template <bool BF16, bool IN_F32, int NV>
 __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) {
+  // The row's data is asked for first; which segment (= whose gain and shift) the row
+  // belongs to is found while it is on its way, in a copy of the segment offsets that the
+  // workgroup put into LDS with one coalesced read (a search through global memory is a
+  // chain of ten dependent round trips per wavefront).
+  __shared__ int seg_s[kMaxRequests + 1];
   const int lane = threadIdx.x & 63;
-  const int srow = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (srow >= a.n_rows) return;
-  int lo = 0, hi = rt.n_segments[0];
-  while (hi - lo > 1) {
-    int mid = (lo + hi) >> 1;
-    if (rt.seg_tok_off[mid] <= srow) lo = mid; else hi = mid;
-  }
-  const size_t slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
+  const int srow = min(blockIdx.x * 4 + (int)(threadIdx.x >> 6), a.n_rows - 1);   // surplus wavefronts redo the last row
   const size_t row = (size_t)rt.row_src[srow];
   constexpr int d = NV * 256;
   constexpr bool in_f32 = IN_F32 || !BF16;
   f32x4 v[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] = load4(a.in, row * d + i * 256 + lane * 4, in_f32);
+  const int G = rt.n_segments[0];
+  for (int i = threadIdx.x; i <= G; i += 256) seg_s[i] = rt.seg_tok_off[i];
+  __syncthreads();
+  int lo = 0, hi = G;
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (seg_s[mid] <= srow) lo = mid; else hi = mid;
+  }
+  const size_t slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
   float s = 0.0f;
 #pragma unroll
-  for (int i = 0; i < NV; ++i)
-    {
-      v[i] = load4(a.in, row * d + i * 256 + lane * 4, in_f32);
-      s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
-    }
+  for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
   const float mean = wave_sum(s) / (float)d;
   float q = 0.0f;
 #pragma unroll
