@@ -1,0 +1,313 @@
+// The paper's bottleneck adapter over a mixed-tenant batch (Sec. 3.2.2, batched as in
+// Sec. 6.3), one kernel:  Y = X + Up_t(ReLU(Down_t(X))),  Down_t: d -> 64,  Up_t: 64 -> d,
+// bf16 storage, fp32 accumulation, Y rounded once.
+//
+// With a 64-wide bottleneck the block moves 4 d bytes per token for 256 d flops per token:
+// far below the machine balance, so the kernel is organised around the HBM stream and not
+// around the MFMA pipes.  A workgroup (8 wavefronts, one per compute unit) walks a
+// contiguous range of 32-row units of the tenant-sorted batch.  A unit's rows are copied
+// straight into LDS (full 128-byte lines, rows gathered through row_src), both
+// projections run out of LDS and registers, the result replaces the rows in LDS, and the
+// same rows stream back out with 16-byte stores: X is read once and Y written once.
+// Two row buffers alternate, so the copies of the unit after next run under this unit's
+// arithmetic; wavefronts 0-3 issue the copies and wavefronts 4-7 the stores, which keeps
+// each wavefront's memory counter to one kind of access (loads return in order among
+// loads only).
+//
+// The tenant's two matrices live in registers for as long as the units stay in one
+// segment: at load time they are laid out in MFMA operand order (pack_adapter_operand
+// below), so a reload is a handful of 1 KB coalesced reads.
+//
+//   Down:  wavefront (cb, kq) multiplies the unit by column block cb of Down over its
+//          quarter kq of d; the four partial sums per element meet in LDS (fixed order of
+//          addition), where bias and ReLU are applied and the 32 x 64 result is rounded to
+//          bf16 once, as the two-kernel path does between its GEMMs.
+//   Up:    wavefront w owns output columns [w d/8, (w+1) d/8); it adds bias and the
+//          unit's own rows from LDS and writes the rounded sum back in place.
+#include "hmi_kernels.h"
+
+namespace hmi {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+constexpr int RT = 32;            // rows of a unit
+constexpr int RANK = 64;          // bottleneck width
+constexpr int NTH = 512;
+constexpr int MAX_UNITS = 64;     // units one workgroup may be handed
+constexpr int PART_BYTES = 4 * RT * RANK * 4;   // four partial sums of the 32 x 64 bottleneck, fp32
+constexpr int MID_BYTES = RT * RANK * 2;
+constexpr int RS_BYTES = MAX_UNITS * RT * 4;
+constexpr int DESC_BYTES = (MAX_UNITS * 4 + 4) * 4;
+
+#define HMI_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+
+__device__ __forceinline__ float bf2f(uint32_t u16) { return __uint_as_float(u16 << 16); }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+template <int NV>
+struct Shape {
+  static constexpr int CH = NV * 32;          // 16-byte chunks of a row (d = 256 NV)
+  static constexpr int ROWB = CH * 16;
+  static constexpr int BUF = RT * ROWB;
+  static constexpr int KS = NV * 16;          // 16-wide k-steps over d
+  static constexpr int KSW = KS / 4;          // ... per wavefront of the down-projection
+  static constexpr int NJ = RT * CH / 256;    // copies (stores) per lane and unit
+  static constexpr int OFF_PART = 2 * BUF;
+  static constexpr int OFF_MID = OFF_PART + PART_BYTES;
+  static constexpr int OFF_RS = OFF_MID + MID_BYTES;
+  static constexpr int OFF_DESC = OFF_RS + RS_BYTES;
+  static constexpr int LDS = OFF_DESC + DESC_BYTES;
+};
+
+// LDS layouts (all XOR swizzles act on 16-byte chunk indices, so that the 16 lanes that
+// the LDS serves together hit 16 different chunks of its 256-byte bank line):
+//   row buffer   row r, position p holds the row's chunk p ^ (r & 15)
+//   partial sum  [kq][row r][16 chunks of 4 fp32], chunk q at position q ^ (r & 15)
+//   bottleneck   row r is 128 bytes (64 bf16), chunk c at position c ^ ((r >> 1) & 7)
+template <int NV>
+__global__ __launch_bounds__(NTH) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void adapter_bf16_kernel(AdapterArgs a, Route rt) {
+  using S = Shape<NV>;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = lane & 31, h = lane >> 5;     // MFMA: token row of the unit, k-half
+  int* desc = reinterpret_cast<int*>(smem + S::OFF_DESC);
+  int* rs = reinterpret_cast<int*>(smem + S::OFF_RS);
+
+  // ---- which units are mine, which of them hold rows, and where those rows live
+  const int U = a.n_tiles128 * 4;
+  const int u_begin = (int)((long long)blockIdx.x * U / gridDim.x);
+  const int u_end = (int)((long long)(blockIdx.x + 1) * U / gridDim.x);
+  if (wave == 0) {
+    const int u = u_begin + lane;
+    int row0 = 0, rows = 0, slot = 0;
+    if (u < u_end) {
+      const int t = u >> 2;
+      const int seg = rt.tile_seg[a.which_tiles][t];
+      row0 = rt.tile_row0[a.which_tiles][t] + (u & 3) * RT;
+      rows = min(RT, rt.seg_tok_off[seg + 1] - row0);
+      slot = rt.seg_slot[seg];
+    }
+    const unsigned long long mask = __ballot(rows > 0);
+    if (rows > 0) {
+      const int pos = __popcll(mask & ((1ull << lane) - 1ull));
+      desc[pos * 4 + 0] = row0; desc[pos * 4 + 1] = rows; desc[pos * 4 + 2] = slot;
+    }
+    if (lane == 0) desc[MAX_UNITS * 4] = __popcll(mask);
+  }
+  __syncthreads();
+  const int m = desc[MAX_UNITS * 4];
+  if (m == 0) return;
+  for (int idx = tid; idx < m * RT; idx += NTH) {
+    const int u = idx >> 5, r = idx & 31;
+    rs[idx] = rt.row_src[desc[u * 4] + min(r, desc[u * 4 + 1] - 1)];   // surplus rows of a short unit repeat its last row
+  }
+
+  const int cb = wave & 1, kq = wave >> 1;    // down-projection role
+  bf16x8 wd[S::KSW], wu[NV][4];
+  u32x4 bu[NV][2];   // up-projection bias of my columns, packed bf16 pairs
+  f32x4 bd4;
+  int cur_slot = -1;
+
+  // copies unit ui into row buffer b (wavefronts 0-3; a lane moves NJ chunks of 16 bytes)
+  const char* X = reinterpret_cast<const char*>(a.X);
+  char* Y = reinterpret_cast<char*>(a.Y);
+#define HMI_ISSUE_COPIES(UI, B)                                                                    \
+  {                                                                                                \
+    _Pragma("unroll") for (int jj = 0; jj < S::NJ; ++jj) {                                         \
+      const int c_ = jj * 256 + tid, row_ = c_ / S::CH, p_ = c_ % S::CH;                           \
+      const char* src_ = X + (size_t)rs[(UI) * RT + row_] * S::ROWB + ((p_ ^ (row_ & 15)) << 4);   \
+      lds_ptr_t dst_ = (lds_ptr_t)(smem + (B) * S::BUF + (jj * 256 + wave * 64) * 16);             \
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)src_, dst_, 16, 0, 0);                           \
+    }                                                                                              \
+  }
+
+  __syncthreads();   // rs complete
+  if (wave < 4) {
+    HMI_ISSUE_COPIES(0, 0)
+    if (m > 1) HMI_ISSUE_COPIES(1, 1)
+  }
+
+  for (int i = 0; i < m; ++i) {
+    const int b = i & 1;
+    unsigned char* buf = smem + b * S::BUF;
+    const int rows = desc[i * 4 + 1], slot = desc[i * 4 + 2];
+    if (slot != cur_slot) {   // same for the whole workgroup
+      cur_slot = slot;
+      const char* base = a.pool + (size_t)slot * a.slot_stride;
+      const bf16x8* pwd = reinterpret_cast<const bf16x8*>(base + a.wd_off) + ((cb * S::KS + kq * S::KSW) * 64 + lane);
+#pragma unroll
+      for (int s = 0; s < S::KSW; ++s) wd[s] = pwd[s * 64];
+      const bf16x8* pwu = reinterpret_cast<const bf16x8*>(base + a.wu_off) + (wave * NV * 4 * 64 + lane);
+#pragma unroll
+      for (int c = 0; c < NV; ++c)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wu[c][s] = pwu[(c * 4 + s) * 64];
+#pragma unroll
+      for (int c = 0; c < NV; ++c) {
+        const u32x4* pb = reinterpret_cast<const u32x4*>(base + a.bu_off + ((wave * NV + c) * 32 + h * 16) * 2);
+        bu[c][0] = pb[0]; bu[c][1] = pb[1];
+      }
+      const u32x2 d2 = *reinterpret_cast<const u32x2*>(base + a.bd_off + (tid & 15) * 8);
+      bd4 = f32x4{bf2f(d2[0] & 0xFFFFu), bf2f(d2[0] >> 16), bf2f(d2[1] & 0xFFFFu), bf2f(d2[1] >> 16)};
+    }
+    if (i == 0) {   // the first unit's rows must have landed (later units: see the end of the loop)
+      if (wave < 4) { if (m > 1) { HMI_WAIT_VMCNT(S::NJ); } else { HMI_WAIT_VMCNT(0); } }
+      __syncthreads();
+    }
+
+    // ---- Down: partial[kq] = X[32, my quarter of d] * Down[cb block, same quarter]^T
+    {
+      f32x16 acc = {};
+      const unsigned char* xr = buf + j * S::ROWB;
+#pragma unroll
+      for (int s = 0; s < S::KSW; ++s) {
+        const int p0 = 2 * (kq * S::KSW + s) + h;
+        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xr + ((p0 ^ (j & 15)) << 4));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd[s], xf, acc, 0, 0, 0);
+      }
+      unsigned char* pr = smem + S::OFF_PART + kq * (RT * RANK * 4) + j * (RANK * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int q = cb * 8 + h * 4 + e;
+        *reinterpret_cast<f32x4*>(pr + ((q ^ (j & 15)) << 4)) = f32x4{acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
+      }
+    }
+    __syncthreads();
+    // ---- bottleneck: sum of the four quarters + bias, ReLU, one rounding to bf16
+    {
+      const int row = tid >> 4, q = tid & 15;
+      const unsigned char* pr = smem + S::OFF_PART + row * (RANK * 4) + ((q ^ (row & 15)) << 4);
+      f32x4 v = *reinterpret_cast<const f32x4*>(pr);
+#pragma unroll
+      for (int k = 1; k < 4; ++k) v += *reinterpret_cast<const f32x4*>(pr + k * (RT * RANK * 4));
+      v += bd4;
+      u32x2 o;
+      o[0] = pack_bf16(fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f));
+      o[1] = pack_bf16(fmaxf(v[2], 0.0f), fmaxf(v[3], 0.0f));
+      *reinterpret_cast<u32x2*>(smem + S::OFF_MID + row * 128 + (((q >> 1) ^ ((row >> 1) & 7)) << 4) + (q & 1) * 8) = o;
+    }
+    __syncthreads();
+    // ---- Up: my d/8 output columns, added to the unit's rows in place
+    {
+      bf16x8 mf[4];
+      const unsigned char* mr = smem + S::OFF_MID + j * 128;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) mf[s] = *reinterpret_cast<const bf16x8*>(mr + (((2 * s + h) ^ ((j >> 1) & 7)) << 4));
+      unsigned char* xr = buf + j * S::ROWB;
+#pragma unroll
+      for (int c = 0; c < NV; ++c) {
+        f32x16 acc;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] = bf2f(bu[c][0][e] & 0xFFFFu); acc[2 * e + 1] = bf2f(bu[c][0][e] >> 16);
+          acc[8 + 2 * e] = bf2f(bu[c][1][e] & 0xFFFFu); acc[8 + 2 * e + 1] = bf2f(bu[c][1][e] >> 16);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[c][s], mf[s], acc, 0, 0, 0);
+        const int p0 = (wave * NV + c) * 4 + 2 * h;
+        u32x4* x0 = reinterpret_cast<u32x4*>(xr + ((p0 ^ (j & 15)) << 4));
+        u32x4* x1 = reinterpret_cast<u32x4*>(xr + (((p0 + 1) ^ (j & 15)) << 4));
+        const u32x4 v0 = *x0, v1 = *x1;
+        u32x4 o0, o1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          o0[e] = pack_bf16(acc[2 * e] + bf2f(v0[e] & 0xFFFFu), acc[2 * e + 1] + bf2f(v0[e] >> 16));
+          o1[e] = pack_bf16(acc[8 + 2 * e] + bf2f(v1[e] & 0xFFFFu), acc[8 + 2 * e + 1] + bf2f(v1[e] >> 16));
+        }
+        *x0 = o0; *x1 = o1;
+      }
+    }
+    __syncthreads();
+    // ---- wavefronts 4-7 stream the finished rows out; wavefronts 0-3 make sure the next
+    //      unit's rows have landed.  After the barrier the buffer is free for unit i + 2.
+    if (wave >= 4) {
+      const int t2 = tid - 256;
+#pragma unroll 4
+      for (int jj = 0; jj < S::NJ; ++jj) {
+        const int c = jj * 256 + t2, row = c / S::CH, p = c % S::CH;
+        if (row < rows) {
+          const u32x4 v = *reinterpret_cast<const u32x4*>(buf + c * 16);
+          *reinterpret_cast<u32x4*>(Y + (size_t)rs[i * RT + row] * S::ROWB + ((p ^ (row & 15)) << 4)) = v;
+        }
+      }
+    } else if (i + 1 < m) {
+      HMI_WAIT_VMCNT(0);
+    }
+    __syncthreads();
+    if (wave < 4 && i + 2 < m) HMI_ISSUE_COPIES(i + 2, b)
+  }
+#undef HMI_ISSUE_COPIES
+}
+
+template <int NV>
+void launch_nv(const AdapterArgs& a, const Route& rt, hipStream_t s) {
+  using S = Shape<NV>;
+  static bool attr_set = false;
+  static int n_cu = 0;
+  auto kern = adapter_bf16_kernel<NV>;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
+    attr_set = true;
+  }
+  if (n_cu == 0) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) n_cu = 256;
+  }
+  const long long U = (long long)a.n_tiles128 * 4;
+  if (U <= 0) return;
+  long long grid = U < n_cu ? U : n_cu;                               // one workgroup per compute unit ...
+  const long long need = (U + MAX_UNITS - 1) / MAX_UNITS;            // ... unless that hands a workgroup
+  if (grid < need) grid = need;                                       //     more units than it can list
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTH), S::LDS, s, a, rt);
+}
+
+}  // namespace
+
+// Operand order: 1 KB blocks, one per (32-row block, 16-wide k-step), k-steps innermost.
+// Lane l of a block holds the 8 elements [16 s + 8 (l / 32), +8) of the block's row
+// perm(l % 32), where perm places the rows so that output register r of lane half hh of
+// the 32x32x16 MFMA is the block's row 16 hh + r.
+void pack_adapter_operand(void* dst, const void* src, int rows, int cols) {
+  uint16_t* o = static_cast<uint16_t*>(dst);
+  const uint16_t* in = static_cast<const uint16_t*>(src);
+  const int ks = cols / 16;
+  for (int rb = 0; rb < rows / 32; ++rb)
+    for (int s = 0; s < ks; ++s)
+      for (int l = 0; l < 64; ++l) {
+        const int i = l & 31;
+        const int row = rb * 32 + ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3);
+        const uint16_t* from = in + (size_t)row * cols + s * 16 + 8 * (l >> 5);
+        uint16_t* to = o + (((size_t)rb * ks + s) * 64 + l) * 8;
+        for (int e = 0; e < 8; ++e) to[e] = from[e];
+      }
+}
+
+bool adapter_bf16_supported(int d, int rank) { return rank == RANK && d % 256 == 0 && d >= 256 && d <= 768; }
+
+// Preconditions (checked by the caller): adapter_bf16_supported(d, rank); which_tiles names
+// the list of 128-row m-tiles and n_tiles128 its length; both matrices of every slot in
+// the batch are in MFMA operand order; X and Y are distinct, 16-byte aligned [N, d] arrays.
+void launch_adapter_bf16(const AdapterArgs& a, const Route& rt, hipStream_t s) {
+  switch (a.d / 256) {
+    case 1: return launch_nv<1>(a, rt, s);
+    case 2: return launch_nv<2>(a, rt, s);
+    default: return launch_nv<3>(a, rt, s);
+  }
+}
+
+}  // namespace hmi

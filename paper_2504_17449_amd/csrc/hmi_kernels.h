@@ -70,6 +70,21 @@ void launch_gemm_bf16_p256(const GemmArgs& g, const Route& rt, hipStream_t s);
 constexpr int kBf16TileM0 = 256, kBf16TileM1 = 128;  // heights of the two m-tile lists of bf16 pools
 constexpr int kF32TileM = 64;
 
+// Fused bottleneck adapter (bf16, rank 64): Y = X + Up_t(ReLU(Down_t(X))), rows addressed
+// through row_src like the GEMMs.  Both matrices must be stored in MFMA operand order
+// (pack_adapter_operand) inside the slot images.
+struct AdapterArgs {
+  const void* X; void* Y;             // bf16 [N, d], distinct
+  const char* pool; size_t slot_stride;
+  size_t wd_off, bd_off, wu_off, bu_off;  // byte offsets inside a slot (layer included)
+  int d;
+  int which_tiles, n_tiles128;        // index and length of the list of 128-row m-tiles
+};
+bool adapter_bf16_supported(int d, int rank);
+void launch_adapter_bf16(const AdapterArgs& a, const Route& rt, hipStream_t s);
+// HOST: [rows, cols] row-major bf16 -> operand order (rows % 32 == 0, cols % 16 == 0, same size).
+void pack_adapter_operand(void* dst, const void* src, int rows, int cols);
+
 // Row LayerNorm with per-tenant gain/shift looked up through the route.
 // in: fp32 (in_f32) or storage dtype; writes out_f32 (fp32, may be null) and/or
 // out_st (storage dtype, may be null).  All [N, d] in original packed order.

@@ -101,6 +101,7 @@ struct hmi_pool {
   Route rt{};
   int last_R = 0;
   int tile_m[2] = {256, 128};
+  bool adapter_fused = false;  // single-layer bf16 adapter pool: matrices kept in operand order, one kernel
 
   // workspaces
   char *w_qkv = nullptr, *w_ctx = nullptr, *w_hmid = nullptr, *w_act = nullptr;
@@ -251,6 +252,15 @@ struct ProfSpan {
   ~ProfSpan() { if (b) (void)hipEventRecord(b, p->compute); }
 };
 
+// Writes one (tenant, layer) image from the caller's canonical tensors.
+void write_image(const hmi_pool* p, char* img, const void* const* tensors) {
+  for (size_t i = 0; i < p->tl.size(); ++i) {
+    if (p->adapter_fused && i == T_W1) pack_adapter_operand(img + p->tl[i].off, tensors[i], p->cfg.d_ff, p->cfg.d_model);
+    else if (p->adapter_fused && i == T_W2) pack_adapter_operand(img + p->tl[i].off, tensors[i], p->cfg.d_model, p->cfg.d_ff);
+    else memcpy(img + p->tl[i].off, tensors[i], p->tl[i].bytes);
+  }
+}
+
 int bits_for(int n) {
   int b = 1;
   while ((1ll << b) < n) ++b;
@@ -290,6 +300,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   p->esize = p->bf16 ? 2 : 4;
   p->tile_m[0] = p->bf16 ? kBf16TileM0 : kF32TileM;
   p->tile_m[1] = p->bf16 ? kBf16TileM1 : 0;
+  p->adapter_fused = p->bf16 && c.block == HMI_BLOCK_ADAPTER && c.n_layers == 1 && adapter_bf16_supported(c.d_model, c.d_ff);
   size_t off = 0;
   for (auto& sh : tensor_shapes(c)) {
     const size_t bytes = (size_t)sh.first * (sh.second ? sh.second : 1) * p->esize;
@@ -424,7 +435,7 @@ int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
       HIP_TRY(p, hipStreamSynchronize(p->copy));
     }
     char* img = p->host_img[tenant] + (size_t)layer * p->image_bytes;
-    for (int i = 0; i < n_tensors; ++i) memcpy(img + p->tl[i].off, tensors[i], p->tl[i].bytes);
+    write_image(p, img, tensors);
     p->loaded[(size_t)tenant * L + layer] = 1;
     if (slot < 0 && !p->free_slots.empty()) slot = acquire_slot(p, tenant, 0);
     if (slot >= 0) {
@@ -446,7 +457,7 @@ int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
   const int si = p->stage_i;
   p->stage_i ^= 1;
   HIP_TRY(p, hipEventSynchronize(p->stage_ev[si]));  // staging buffer free again
-  for (int i = 0; i < n_tensors; ++i) memcpy(p->stage[si] + p->tl[i].off, tensors[i], p->tl[i].bytes);
+  write_image(p, p->stage[si], tensors);
   char* dst = p->d_pool + (size_t)slot * p->slot_stride + (size_t)layer * p->image_bytes;
   HIP_TRY(p, hipMemcpyAsync(dst, p->stage[si], p->image_bytes, hipMemcpyHostToDevice, p->copy));
   HIP_TRY(p, hipEventRecord(p->stage_ev[si], p->copy));
@@ -648,6 +659,16 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
         lnorm(p->w_z, true, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, T_LNG, T_LNB);
         break;
       case HMI_BLOCK_ADAPTER:
+        if (p->adapter_fused) {
+          AdapterArgs a{};
+          a.X = x; a.Y = y; a.pool = p->d_pool; a.slot_stride = p->slot_stride;
+          a.wd_off = lay + p->tl[T_W1].off; a.bd_off = lay + p->tl[T_B1].off;
+          a.wu_off = lay + p->tl[T_W2].off; a.bu_off = lay + p->tl[T_B2].off;
+          a.d = d; a.which_tiles = 1; a.n_tiles128 = n_mtiles[1];
+          ProfSpan ps(p, HMI_KERNEL_GEMM);
+          launch_adapter_bf16(a, rt, s);
+          break;
+        }
         gemm(in_st, d, T_W1, T_B1, f, d, EPI_BIAS_RELU, p->w_hmid, f, nullptr, 0, false, false, nullptr);
         if (last)
           gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, y, d, in_res, d, in_res_f32, f32, nullptr);

@@ -132,6 +132,57 @@ def test_bf16_adapter_rank_64(hmi):
     run_case(hmi, small(synth.BLOCK_ADAPTER, "bf16", d_model=768, d_ff=64, seq_max=128, seq_min=128))
 
 
+@pytest.mark.parametrize("d_model", [256, 512, 768])
+def test_fused_adapter_ragged_large_weights(hmi, d_model):
+    """Single-layer bf16 adapter pools with rank 64 run the one-kernel path (rows through LDS,
+    matrices repacked at load).  The seeded recipe's weights make the adapter's contribution a
+    few percent of |x|, so a misplaced k-chunk or column block would hide under the rounding of
+    y; here x is small and the weights large, so that y is mostly the adapter's own output, and
+    every row is compared.  Lengths 1..150 over 40 tenants: units of 1..32 rows, requests that
+    end inside a unit, segments of several requests, tenants changing inside one workgroup."""
+    from paper_2504_17449_amd import harness
+    rng = np.random.default_rng(100 + d_model)
+    T, R, r = 40, 90, 64
+    wl = small(synth.BLOCK_ADAPTER, "bf16", d_model=d_model, d_ff=r, n_tenants=T, hbm_slots=T, n_requests=R)
+    ids = rng.integers(0, T, R).astype(np.int32)
+    lens = rng.integers(1, 151, R).astype(np.int32)
+    N = int(lens.sum())
+    rb = lambda a: synth.round_to_storage(a.astype(np.float32), "bf16")
+    w = {t: {"w_down": rb(rng.normal(0, 0.2, (r, d_model))), "b_down": rb(rng.normal(0, 0.2, r)),
+             "w_up": rb(rng.normal(0, 0.2, (d_model, r))), "b_up": rb(rng.normal(0, 0.2, d_model))}
+         for t in sorted(set(ids.tolist()))}
+    X = rb(rng.normal(0, 1.0 / 16, (N, d_model)))
+    print(f"case fused adapter d={d_model} R={R} N={N}", flush=True)
+    pool = harness.create_pool(wl, max_requests=R, max_tokens=N)
+    try:
+        for t, wt in w.items():
+            pool.load_tenant(t, 0, [synth.to_storage_bytes(wt[n], "bf16") for n in ("w_down", "b_down", "w_up", "b_up")])
+        x = harness.host_to_device(X, "bf16")
+        y = torch.empty_like(x)
+        pool.forward(0, x, y, ids, lens)
+        torch.cuda.synchronize()
+        check_route(pool, ids, lens)
+        y_gpu = harness.device_to_f64(y)
+        # a second batch on the same pool: other lengths, fewer requests (stale LDS or schedule state would show)
+        ids2, lens2 = ids[:17].copy(), rng.integers(1, 40, 17).astype(np.int32)
+        N2 = int(lens2.sum())
+        y2 = torch.empty_like(x[:N2])
+        pool.forward(0, x[:N2].contiguous(), y2, ids2, lens2)
+        torch.cuda.synchronize()
+        y2_gpu = harness.device_to_f64(y2)
+    finally:
+        pool.close()
+    get = lambda t: {k: v.astype(np.float64) for k, v in w[t].items()}
+    y_ref = O.layer_forward(synth.BLOCK_ADAPTER, X.astype(np.float64), ids, lens, get, 0, 0.0)
+    max_abs, rel, ok = compare(y_gpu, y_ref, np.arange(N), "bf16")
+    print(f"  max_abs={max_abs:.3e} rel_fro={rel:.3e} max|y_ref|={np.abs(y_ref).max():.2f} "
+          f"|y-x|/|y|={np.linalg.norm(y_ref - X) / np.linalg.norm(y_ref):.2f}", flush=True)
+    assert ok, (max_abs, rel)
+    y2_ref = O.layer_forward(synth.BLOCK_ADAPTER, X[:N2].astype(np.float64), ids2, lens2, get, 0, 0.0)
+    max_abs, rel, ok = compare(y2_gpu, y2_ref, np.arange(N2), "bf16")
+    assert ok, (max_abs, rel)
+
+
 def test_bert_ffn_full_size_sampled(hmi):
     wl = synth.WORKLOADS["bert_ffn"]
     ids, _ = synth.batch_ids_lens(wl)
