@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_F32_TFLOPS = 157.3     # fp32 vector
+PEAK_HBM_GBS = 8000.0       # HBM3E, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by a copy kernel of known size in the same run, see --copy-calibration):
 # mean over the FFN1 and FFN2 launches, from profiles/gemm_bf16_p256_bert_ffn.md.
@@ -142,6 +143,15 @@ def main() -> int:
                 "avg_launch_ms": round(gemm_launch_ms, 5), "launches_per_step": launches_per_step,
                 "flop_per_launch": flops_per_launch,
                 "kernel_ms_per_step": {k: round(v["ms"] / args.steps, 5) for k, v in prof.items()}}
+    if wl.block == synth.BLOCK_ADAPTER and bf16 and wl.n_layers == 1:
+        # One fused kernel that moves 4 d bytes per token for 256 d flops per token: bound by HBM.
+        # Algorithmic bytes: x in, y out, and each present tenant's image once.
+        algo_bytes = 2.0 * N * wl.d_model * 2 + len(set(ids.tolist())) * pool.image_bytes()
+        gbs = algo_bytes / (gemm_launch_ms * 1e-3) / 1e9
+        roofline.update({"bound": "hbm", "kernel": "adapter_fused", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                         "bytes_per_launch": algo_bytes})
+        del roofline["flop_per_launch"]
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same batch
     cpu = None

@@ -19,7 +19,7 @@
 // below), so a reload is a handful of 1 KB coalesced reads.
 //
 //   Down:  wavefront (cb, kq) multiplies the unit by column block cb of Down over its
-//          quarter kq of d; the four partial sums per element meet in LDS (fixed order of
+//          quarter kq of d (k-steps 2 kq and 2 kq + 1 of every eight); the four partial sums per element meet in LDS (fixed order of
 //          addition), where bias and ReLU are applied and the 32 x 64 result is rounded to
 //          bf16 once, as the two-kernel path does between its GEMMs.
 //   Up:    wavefront w owns output columns [w d/8, (w+1) d/8); it adds bias and the
@@ -120,21 +120,57 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
   bf16x8 wd[S::KSW], wu[NV][4];
   u32x4 bu[NV][2];   // up-projection bias of my columns, packed bf16 pairs
   f32x4 bd4;
-  int cur_slot = -1;
 
   // copies unit ui into row buffer b (wavefronts 0-3; a lane moves NJ chunks of 16 bytes)
   const char* X = reinterpret_cast<const char*>(a.X);
   char* Y = reinterpret_cast<char*>(a.Y);
+  // A lane's NJ = 4 NV chunks of a unit: chunk jj * 256 + t8 with t8 = tid mod 256.  256 NV
+  // chunks are exactly 8 rows, so chunk (NV g + r3) * 256 + t8 lies in row 8 g + ro[r3] at a
+  // row position that does not depend on g; sw[r3] is that position swizzled for g even.
+  const int t8 = tid & 255;
+  int ro[NV], sw[NV];
+#pragma unroll
+  for (int r3 = 0; r3 < NV; ++r3) {
+    const int c = r3 * 256 + t8;
+    ro[r3] = c / S::CH;
+    sw[r3] = ((c % S::CH) ^ ro[r3]) << 4;
+  }
 #define HMI_ISSUE_COPIES(UI, B)                                                                    \
   {                                                                                                \
-    _Pragma("unroll") for (int jj = 0; jj < S::NJ; ++jj) {                                         \
-      const int c_ = jj * 256 + tid, row_ = c_ / S::CH, p_ = c_ % S::CH;                           \
-      const char* src_ = X + (size_t)rs[(UI) * RT + row_] * S::ROWB + ((p_ ^ (row_ & 15)) << 4);   \
-      lds_ptr_t dst_ = (lds_ptr_t)(smem + (B) * S::BUF + (jj * 256 + wave * 64) * 16);             \
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)src_, dst_, 16, 0, 0);                           \
+    _Pragma("unroll") for (int g_ = 0; g_ < 4; ++g_)                                               \
+      _Pragma("unroll") for (int r3 = 0; r3 < NV; ++r3) {                                          \
+        const char* src_ = X + (size_t)rs[(UI) * RT + 8 * g_ + ro[r3]] * S::ROWB + (sw[r3] ^ ((g_ & 1) << 7)); \
+        lds_ptr_t dst_ = (lds_ptr_t)(smem + (B) * S::BUF + ((g_ * NV + r3) * 256 + wave * 64) * 16); \
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)src_, dst_, 16, 0, 0);                         \
+      }                                                                                            \
+  }
+
+#define HMI_LOAD_WD(SLOT)                                                                          \
+  {                                                                                                \
+    const bf16x8* pwd = reinterpret_cast<const bf16x8*>(a.pool + (size_t)(SLOT) * a.slot_stride + a.wd_off) + \
+                        ((cb * S::KS + 2 * kq) * 64 + lane);                                       \
+    _Pragma("unroll") for (int s = 0; s < S::KSW; ++s)                                             \
+      wd[s] = pwd[((s >> 1) * 8 + (s & 1)) * 64];   /* k-step 8 (s / 2) + 2 kq + s % 2 */          \
+  }
+#define HMI_LOAD_BD(SLOT)                                                                          \
+  {                                                                                                \
+    const u32x2 d2 = *reinterpret_cast<const u32x2*>(a.pool + (size_t)(SLOT) * a.slot_stride + a.bd_off + (tid & 15) * 8); \
+    bd4 = f32x4{bf2f(d2[0] & 0xFFFFu), bf2f(d2[0] >> 16), bf2f(d2[1] & 0xFFFFu), bf2f(d2[1] >> 16)}; \
+  }
+#define HMI_LOAD_WU(SLOT)                                                                          \
+  {                                                                                                \
+    const char* base = a.pool + (size_t)(SLOT) * a.slot_stride;                                    \
+    const bf16x8* pwu = reinterpret_cast<const bf16x8*>(base + a.wu_off) + (wave * NV * 4 * 64 + lane); \
+    _Pragma("unroll") for (int c = 0; c < NV; ++c)                                                 \
+      _Pragma("unroll") for (int s = 0; s < 4; ++s) wu[c][s] = pwu[(c * 4 + s) * 64];              \
+    _Pragma("unroll") for (int c = 0; c < NV; ++c) {                                               \
+      const u32x4* pb = reinterpret_cast<const u32x4*>(base + a.bu_off + ((wave * NV + c) * 32 + h * 16) * 2); \
+      bu[c][0] = pb[0]; bu[c][1] = pb[1];                                                          \
     }                                                                                              \
   }
 
+  int cur_slot = desc[2];
+  HMI_LOAD_WD(cur_slot) HMI_LOAD_BD(cur_slot) HMI_LOAD_WU(cur_slot)
   __syncthreads();   // rs complete
   if (wave < 4) {
     HMI_ISSUE_COPIES(0, 0)
@@ -144,26 +180,11 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
   for (int i = 0; i < m; ++i) {
     const int b = i & 1;
     unsigned char* buf = smem + b * S::BUF;
-    const int rows = desc[i * 4 + 1], slot = desc[i * 4 + 2];
-    if (slot != cur_slot) {   // same for the whole workgroup
-      cur_slot = slot;
-      const char* base = a.pool + (size_t)slot * a.slot_stride;
-      const bf16x8* pwd = reinterpret_cast<const bf16x8*>(base + a.wd_off) + ((cb * S::KS + kq * S::KSW) * 64 + lane);
-#pragma unroll
-      for (int s = 0; s < S::KSW; ++s) wd[s] = pwd[s * 64];
-      const bf16x8* pwu = reinterpret_cast<const bf16x8*>(base + a.wu_off) + (wave * NV * 4 * 64 + lane);
-#pragma unroll
-      for (int c = 0; c < NV; ++c)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wu[c][s] = pwu[(c * 4 + s) * 64];
-#pragma unroll
-      for (int c = 0; c < NV; ++c) {
-        const u32x4* pb = reinterpret_cast<const u32x4*>(base + a.bu_off + ((wave * NV + c) * 32 + h * 16) * 2);
-        bu[c][0] = pb[0]; bu[c][1] = pb[1];
-      }
-      const u32x2 d2 = *reinterpret_cast<const u32x2*>(base + a.bd_off + (tid & 15) * 8);
-      bd4 = f32x4{bf2f(d2[0] & 0xFFFFu), bf2f(d2[0] >> 16), bf2f(d2[1] & 0xFFFFu), bf2f(d2[1] >> 16)};
-    }
+    const int rows = desc[i * 4 + 1];
+    // the tenant of the next unit, if it is another one: its matrices replace this unit's as
+    // soon as each has been used for the last time, so that the reads run under the rest of the unit
+    const int next_slot = i + 1 < m ? desc[(i + 1) * 4 + 2] : cur_slot;
+    const bool reload = next_slot != cur_slot;   // same for the whole workgroup
     if (i == 0) {   // the first unit's rows must have landed (later units: see the end of the loop)
       if (wave < 4) { if (m > 1) { HMI_WAIT_VMCNT(S::NJ); } else { HMI_WAIT_VMCNT(0); } }
       __syncthreads();
@@ -171,12 +192,15 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
 
     // ---- Down: partial[kq] = X[32, my quarter of d] * Down[cb block, same quarter]^T
     {
+      // my k-steps are 8 a + 2 kq + e (a = 0 .. KS/8 - 1, e = 0, 1): the row chunks 16 a + 4 kq + 2 e + h,
+      // whose swizzled position inside the 256-byte group a is the same for every a
       f32x16 acc = {};
       const unsigned char* xr = buf + j * S::ROWB;
+      const unsigned char* x0 = xr + (((4 * kq + h) ^ (j & 15)) << 4);
+      const unsigned char* x1 = xr + (((4 * kq + 2 + h) ^ (j & 15)) << 4);
 #pragma unroll
       for (int s = 0; s < S::KSW; ++s) {
-        const int p0 = 2 * (kq * S::KSW + s) + h;
-        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xr + ((p0 ^ (j & 15)) << 4));
+        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(((s & 1) ? x1 : x0) + (s >> 1) * 256);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd[s], xf, acc, 0, 0, 0);
       }
       unsigned char* pr = smem + S::OFF_PART + kq * (RT * RANK * 4) + j * (RANK * 4);
@@ -186,6 +210,7 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
         *reinterpret_cast<f32x4*>(pr + ((q ^ (j & 15)) << 4)) = f32x4{acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
       }
     }
+    if (reload) HMI_LOAD_WD(next_slot)
     __syncthreads();
     // ---- bottleneck: sum of the four quarters + bias, ReLU, one rounding to bf16
     {
@@ -200,6 +225,7 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
       o[1] = pack_bf16(fmaxf(v[2], 0.0f), fmaxf(v[3], 0.0f));
       *reinterpret_cast<u32x2*>(smem + S::OFF_MID + row * 128 + (((q >> 1) ^ ((row >> 1) & 7)) << 4) + (q & 1) * 8) = o;
     }
+    if (reload) HMI_LOAD_BD(next_slot)
     __syncthreads();
     // ---- Up: my d/8 output columns, added to the unit's rows in place
     {
@@ -231,18 +257,25 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
         *x0 = o0; *x1 = o1;
       }
     }
+    if (reload) HMI_LOAD_WU(next_slot)
+    cur_slot = next_slot;
     __syncthreads();
     // ---- wavefronts 4-7 stream the finished rows out; wavefronts 0-3 make sure the next
     //      unit's rows have landed.  After the barrier the buffer is free for unit i + 2.
     if (wave >= 4) {
-      const int t2 = tid - 256;
-#pragma unroll 4
-      for (int jj = 0; jj < S::NJ; ++jj) {
-        const int c = jj * 256 + t2, row = c / S::CH, p = c % S::CH;
-        if (row < rows) {
-          const u32x4 v = *reinterpret_cast<const u32x4*>(buf + c * 16);
-          *reinterpret_cast<u32x4*>(Y + (size_t)rs[i * RT + row] * S::ROWB + ((p ^ (row & 15)) << 4)) = v;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x4 v[NV];
+        int orow[NV];
+#pragma unroll
+        for (int r3 = 0; r3 < NV; ++r3) {
+          v[r3] = *reinterpret_cast<const u32x4*>(buf + ((g * NV + r3) * 256 + t8) * 16);
+          orow[r3] = rs[i * RT + 8 * g + ro[r3]];
         }
+#pragma unroll
+        for (int r3 = 0; r3 < NV; ++r3)
+          if (8 * g + ro[r3] < rows)
+            *reinterpret_cast<u32x4*>(Y + (size_t)orow[r3] * S::ROWB + (sw[r3] ^ ((g & 1) << 7))) = v[r3];
       }
     } else if (i + 1 < m) {
       HMI_WAIT_VMCNT(0);
@@ -251,6 +284,9 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
     if (wave < 4 && i + 2 < m) HMI_ISSUE_COPIES(i + 2, b)
   }
 #undef HMI_ISSUE_COPIES
+#undef HMI_LOAD_WD
+#undef HMI_LOAD_BD
+#undef HMI_LOAD_WU
 }
 
 template <int NV>

@@ -58,15 +58,24 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int rounds = (R + kRouterThreads - 1) / kRouterThreads;
 
-  // ---- tok_off = exclusive scan of seq_lens in arrival order
+  // ---- tok_off = exclusive scan of seq_lens in arrival order.  The three input arrays may
+  //      live in host memory (a round trip over the host link per dependent read), so each
+  //      is read exactly once, here, all reads in flight together.
   int carry = 0;
-  for (int c = 0; c < rounds; ++c) {
-    int i = c * kRouterThreads + tid;
-    int len = i < R ? rt.seq_lens[i] : 0;
-    int tot;
-    int ex = block_exscan(len, wave_tot, tot) + carry;
-    if (i < R) { tok_s[i] = ex; rt.tok_off[i] = ex; key[0][i] = rt.tenant_ids[i]; val[0][i] = i; }
-    carry += tot;
+  int slot_r[kRounds];
+#pragma unroll
+  for (int c = 0; c < kRounds; ++c) {
+    slot_r[c] = 0;
+    if (c < rounds) {
+      int i = c * kRouterThreads + tid;
+      int len = i < R ? rt.seq_lens[i] : 0;
+      int tenant = i < R ? rt.tenant_ids[i] : 0;
+      slot_r[c] = i < R ? rt.req_slot[i] : 0;
+      int tot;
+      int ex = block_exscan(len, wave_tot, tot) + carry;
+      if (i < R) { tok_s[i] = ex; rt.tok_off[i] = ex; key[0][i] = tenant; val[0][i] = i; }
+      carry += tot;
+    }
   }
   const int N = carry;
   if (tid == 0) { tok_s[R] = N; rt.tok_off[R] = N; }
@@ -120,6 +129,13 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
   }
   const int* sid = key[cur];
   const int* perm = val[cur];
+  int* slot_s = key[cur ^ 1];   // the sort's spare buffer: request -> HBM slot
+#pragma unroll
+  for (int c = 0; c < kRounds; ++c) {
+    int i = c * kRouterThreads + tid;
+    if (c < rounds && i < R) slot_s[i] = slot_r[c];
+  }
+  __syncthreads();
 
   // ---- segments (maximal runs of one tenant) and sorted-token offsets
   int seg_carry = 0, tok_carry = 0;
@@ -127,7 +143,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
     int p = c * kRouterThreads + tid;
     bool in = p < R;
     int head = in && (p == 0 || sid[p] != sid[p - 1]);
-    int len = in ? rt.seq_lens[perm[p]] : 0;
+    int len = in ? tok_s[perm[p] + 1] - tok_s[perm[p]] : 0;
     int tot_h, tot_l;
     int g = block_exscan(head, wave_tot, tot_h) + seg_carry;
     int st = block_exscan(len, wave_tot, tot_l) + tok_carry;
@@ -136,7 +152,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
       stok_s[p] = st;
       if (head) {
         rt.seg_tenant[g] = sid[p];
-        rt.seg_slot[g] = rt.req_slot[perm[p]];
+        rt.seg_slot[g] = slot_s[perm[p]];
         rt.seg_req_off[g] = p;
         rt.seg_tok_off[g] = st;
         segtok_s[g] = st;
