@@ -13,7 +13,8 @@ The per-tenant block is built from the paper's Linear(a) = W a + b and the resid
 shape of its adapter A(a) = Up(phi(Down(a))) + a (Sec. 3.2.2); for the whole-FFN and
 whole-layer blocks the paper defers to BERT / GPT, whose sub-layer equations are used
 (post-LN encoder: LN after each residual; pre-LN decoder: LN before each sub-layer,
-causal attention; exact erf GELU; biased-variance LayerNorm; softmax scaled by
+causal attention; for the shared layer with a per-tenant adapter after the attention
+layer the paper's own description of its fine-tuned layer, Sec. 3.2.2; exact erf GELU; biased-variance LayerNorm; softmax scaled by
 1/sqrt(d_head), never across requests, no padding keys).
 
 All arithmetic is numpy fp64; ``@`` (matmul) and ``scipy.special.erf`` are the only
@@ -36,6 +37,7 @@ BLOCK_FFN = 0
 BLOCK_ENC_POSTLN = 1
 BLOCK_DEC_PRELN = 2
 BLOCK_ADAPTER = 3
+BLOCK_ENC_ADAPTER = 4
 
 
 # --------------------------------------------------------------------------- router
@@ -147,6 +149,17 @@ def adapter_block(x, w):
     return linear(relu(linear(x, w["w_down"], w["b_down"])), w["w_up"], w["b_up"]) + x
 
 
+def encoder_postln_adapter(x, w, n_heads, eps):
+    """The paper's task-adapted higher layer (Sec. 3.2.2, architecture figure (c)): a BERT
+    post-LN encoder layer whose parameters are shared by every tenant, with the tenant's
+    adapter injected after the attention layer.  The adapter A(a) = Up(ReLU(Down(a))) + a
+    acts on the attention layer's output a (output projection included) before the
+    residual connection and its LayerNorm; the feed-forward half is the plain shared one."""
+    a = attention(x, w, n_heads, causal=False)
+    x1 = layer_norm(x + adapter_block(a, w), w["ln1_g"], w["ln1_b"], eps)
+    return layer_norm(x1 + ffn(x1, w), w["ln2_g"], w["ln2_b"], eps)
+
+
 def block_forward(block: int, x: np.ndarray, w: Dict[str, np.ndarray], n_heads: int,
                   eps: float) -> np.ndarray:
     """One request's rows through one tenant's block."""
@@ -158,6 +171,8 @@ def block_forward(block: int, x: np.ndarray, w: Dict[str, np.ndarray], n_heads: 
         return decoder_preln(x, w, n_heads, eps)
     if block == BLOCK_ADAPTER:
         return adapter_block(x, w)
+    if block == BLOCK_ENC_ADAPTER:
+        return encoder_postln_adapter(x, w, n_heads, eps)
     raise ValueError(f"unknown block {block}")
 
 

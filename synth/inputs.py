@@ -22,6 +22,9 @@ BLOCK_FFN = 0          # Y = LN(X + W2 GELU(W1 X + b1) + b2)
 BLOCK_ENC_POSTLN = 1   # bidirectional attention + FFN, LayerNorm after each residual
 BLOCK_DEC_PRELN = 2    # causal attention + FFN, LayerNorm before each sub-layer
 BLOCK_ADAPTER = 3      # Y = X + Up(ReLU(Down(X)))  (bottleneck adapter, Sec. 3.2.2)
+BLOCK_ENC_ADAPTER = 4  # shared post-LN encoder layer + per-tenant adapter after its attention layer (Sec. 3.2.2)
+
+SHARED = 0x7FFFFFFF    # "tenant" key of the parameters every tenant shares
 
 _TAG_WEIGHT, _TAG_X, _TAG_IDS, _TAG_LENS = 1, 2, 3, 4
 
@@ -45,6 +48,7 @@ class Workload:
     hbm_slots: int        # tenants resident in HBM at once
     host_tier: bool       # pinned-host pool + HBM cache + swap-in
     seed: int = 0
+    adapter_rank: int = 0  # BLOCK_ENC_ADAPTER: bottleneck width of the per-tenant adapter
 
     def scaled(self, **kw) -> "Workload":
         """Same recipe at another size (tests use reduced tenant / request counts)."""
@@ -64,6 +68,10 @@ WORKLOADS = {
                          32, 512, "zipf", 1.0, 1e-5, 2000, False),
     "hbert_10k": Workload("hbert_10k", BLOCK_ENC_POSTLN, "bf16", 768, 3072, 12, 1, 10000, 1024,
                           16, 256, "zipf", 0.8, 1e-12, 2000, True),
+    # The paper's own serving layer: the 6 higher BERT-base layers shared by all tenants, each
+    # with the tenant's adapter after its attention layer (Sec. 3.2.2, Sec. 3.3 footnote).
+    "hbert_shared_adapter": Workload("hbert_shared_adapter", BLOCK_ENC_ADAPTER, "bf16", 768, 3072, 12, 6, 1000,
+                                     512, 128, 128, "zipf", 1.1, 1e-12, 1000, False, adapter_rank=64),
     # Paper-exact bottleneck adapter (Sec. 3.2.2); rank 64 is this build's reading.
     "hbert_adapter": Workload("hbert_adapter", BLOCK_ADAPTER, "bf16", 768, 64, 0, 1, 1000, 512,
                               128, 128, "zipf", 1.1, 0.0, 1000, False),
@@ -78,6 +86,9 @@ def tensor_specs(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
     """
     d, f = wl.d_model, wl.d_ff
     ffn = [("w1", (f, d), "w"), ("b1", (f,), "b"), ("w2", (d, f), "w"), ("b2", (d,), "b")]
+    if wl.block == BLOCK_ENC_ADAPTER:
+        r = wl.adapter_rank
+        return [("w_down", (r, d), "w"), ("b_down", (r,), "b"), ("w_up", (d, r), "w"), ("b_up", (d,), "b")]
     if wl.block == BLOCK_FFN:
         return ffn + [("ln_g", (d,), "g"), ("ln_b", (d,), "beta")]
     if wl.block in (BLOCK_ENC_POSTLN, BLOCK_DEC_PRELN):
@@ -89,6 +100,13 @@ def tensor_specs(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
         return [("w_down", (f, d), "w"), ("b_down", (f,), "b"),
                 ("w_up", (d, f), "w"), ("b_up", (d,), "b")]
     raise ValueError(f"unknown block {wl.block}")
+
+
+def shared_specs(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
+    """Tensors of one layer that every tenant shares (BLOCK_ENC_ADAPTER: the encoder layer)."""
+    if wl.block != BLOCK_ENC_ADAPTER:
+        return []
+    return tensor_specs(replace(wl, block=BLOCK_ENC_POSTLN))
 
 
 # ---------------------------------------------------------------- dtype packing
@@ -200,6 +218,15 @@ def tenant_storage(wl: Workload, tenant: int, layer: int = 0) -> List[np.ndarray
     patterns as uint16, or fp32).  Mostly zero-copy views of the master sequence."""
     return [_tensor(wl, tenant, layer, i, shape, kind, True)
             for i, (_, shape, kind) in enumerate(tensor_specs(wl))]
+
+
+def shared_tensors(wl: Workload, layer: int = 0) -> List[np.ndarray]:
+    """The shared tensors of one layer in canonical order (same distributions as tenant_tensors)."""
+    return [_tensor(wl, SHARED, layer, 100 + i, shape, kind, False) for i, (_, shape, kind) in enumerate(shared_specs(wl))]
+
+
+def shared_storage(wl: Workload, layer: int = 0) -> List[np.ndarray]:
+    return [_tensor(wl, SHARED, layer, 100 + i, shape, kind, True) for i, (_, shape, kind) in enumerate(shared_specs(wl))]
 
 
 def hidden_states(wl: Workload, request: int, seq_len: int, batch: int = 0) -> np.ndarray:

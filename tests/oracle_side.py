@@ -10,11 +10,13 @@ from oracle import hmi_oracle as O
 
 def weights_of(wl: synth.Workload, layer: int):
     names = [n for n, _, _ in synth.tensor_specs(wl)]
+    shared = {n: a.astype(np.float64) for (n, _, _), a in zip(synth.shared_specs(wl), synth.shared_tensors(wl, layer))}
     cache = {}
 
     def get(t: int):
         if t not in cache:
-            cache[t] = {n: a.astype(np.float64) for n, a in zip(names, synth.tenant_tensors(wl, t, layer))}
+            cache[t] = dict(shared)
+            cache[t].update({n: a.astype(np.float64) for n, a in zip(names, synth.tenant_tensors(wl, t, layer))})
         return cache[t]
     return get
 

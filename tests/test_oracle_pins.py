@@ -176,6 +176,63 @@ def test_adapter_block_hand_worked():
                                atol=1e-13)
 
 
+def adapter_weights(seed, d, r, scale=0.3):
+    g = np.random.default_rng(seed)
+    n = lambda *s: g.standard_normal(s) * scale  # noqa: E731
+    return {"w_down": n(r, d), "b_down": n(r), "w_up": n(d, r), "b_up": n(d)}
+
+
+def test_shared_layer_with_adapter_hand_worked():
+    """Sec. 3.2.2: the adapter sits after the attention layer, on that layer's output, inside the
+    residual.  One token (softmax of one score is 1), d = 2, identity value / output matrices:
+      a   = Wo (Wv x + bv) + bo = x + bo = [1,2] + [1,-1] = [2,1]
+      A(a)= a + Up ReLU(Down a) = [2,1] + [2,3]*ReLU(2-1) + [0.5,0] = [4.5,4]
+      x1  = LN1(x + A(a)) = LN([5.5,6]) = [-1,1]            (gain 1, shift 0, eps 0)
+      y   = LN2(x1 + b2) = LN([-1,1] + [1,3]) = LN([0,4]) = [-1,1] * [2,3] + [0.5,-0.5] = [-1.5,2.5]
+    (W1 = 0, b1 = 0 make the feed-forward half output b2.)  With Down = [-1,1] the ReLU closes:
+      A(a) = [2.5,1]; x + A(a) = [3.5,3] -> x1 = [1,-1]; + [1,3] = [2,2]: use b2 = [1,4] -> [2,3] -> y = [-1.5,2.5]."""
+    I, Z = np.eye(2), np.zeros((2, 2))
+    w = {"wqkv": np.vstack([Z, Z, I]), "bqkv": np.zeros(6), "wo": I, "bo": np.array([1.0, -1.0]),
+         "ln1_g": np.ones(2), "ln1_b": np.zeros(2), "w1": np.zeros((3, 2)), "b1": np.zeros(3),
+         "w2": np.zeros((2, 3)), "b2": np.array([1.0, 3.0]), "ln2_g": np.array([2.0, 3.0]), "ln2_b": np.array([0.5, -0.5]),
+         "w_down": np.array([[1.0, -1.0]]), "b_down": np.zeros(1), "w_up": np.array([[2.0], [3.0]]),
+         "b_up": np.array([0.5, 0.0])}
+    x = np.array([[1.0, 2.0]])
+    np.testing.assert_allclose(O.encoder_postln_adapter(x, w, 1, 0.0), [[-1.5, 2.5]], rtol=0, atol=1e-14)
+    w2 = dict(w, w_down=np.array([[-1.0, 1.0]]), b2=np.array([1.0, 4.0]))
+    np.testing.assert_allclose(O.encoder_postln_adapter(x, w2, 1, 0.0), [[-1.5, 2.5]], rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("S", [1, 5])
+def test_shared_layer_with_adapter_against_scalar_brute_force(S):
+    d, f, r, h = 4, 6, 3, 2
+    w = dict(enc_weights(31 + S, d, f, 0.7), **adapter_weights(41 + S, d, r, 0.7))
+    x = rnd(51 + S, S, d)
+    wl, xl = as_lists(w), x.tolist()
+    a = bf_attention(xl, wl, h, False)
+    mid = [[max(v, 0.0) for v in row] for row in bf_linear(a, wl["w_down"], wl["b_down"])]
+    a2 = bf_add(a, bf_linear(mid, wl["w_up"], wl["b_up"]))
+    x1 = [bf_ln(row, wl["ln1_g"], wl["ln1_b"], 1e-12) for row in bf_add(xl, a2)]
+    want = [bf_ln(row, wl["ln2_g"], wl["ln2_b"], 1e-12) for row in bf_add(x1, bf_ffn(x1, wl))]
+    np.testing.assert_allclose(O.encoder_postln_adapter(x, w, h, 1e-12), want, rtol=1e-11, atol=1e-12)
+
+
+def test_shared_layer_with_silent_adapter_is_the_plain_encoder_layer():
+    """Up = 0, b_up = 0: A(a) = a, so the layer is the shared encoder layer itself, which the
+    library-layer pin covers; a tenant whose up-projection is not zero differs."""
+    d, f, r, h = 8, 16, 4, 2
+    w = dict(enc_weights(7, d, f), **adapter_weights(8, d, r))
+    x = rnd(9, 6, d)
+    quiet = dict(w, w_up=np.zeros((d, r)), b_up=np.zeros(d))
+    assert np.array_equal(O.encoder_postln_adapter(x, quiet, h, 1e-12), O.encoder_postln(x, w, h, 1e-12))
+    assert np.abs(O.encoder_postln_adapter(x, w, h, 1e-12) - O.encoder_postln(x, w, h, 1e-12)).max() > 1e-3
+    # through the batch loop: two tenants share the layer and differ only in their adapters
+    bank = {0: quiet, 1: w}
+    Y = O.layer_forward(O.BLOCK_ENC_ADAPTER, np.concatenate([x, x]), [1, 0], [6, 6], lambda t: bank[t], h, 1e-12)
+    assert np.array_equal(Y[6:], O.encoder_postln(x, w, h, 1e-12))
+    assert np.array_equal(Y[:6], O.encoder_postln_adapter(x, w, h, 1e-12))
+
+
 def test_attention_seq_len_one_collapses_to_linear_chain():
     d, f, h = 8, 16, 2
     w = enc_weights(5, d, f)
@@ -444,6 +501,8 @@ MUTANTS = {
                         / np.sqrt(x.var(-1, ddof=1, keepdims=True) + eps) * g + b),
     "ln_eps_outside": ("layer_norm", lambda x, g, b, eps: (x - x.mean(-1, keepdims=True))
                        / (np.sqrt(x.var(-1, keepdims=True)) + eps) * g + b),
+    "adapter_no_skip": ("adapter_block", lambda x, w: np.maximum(x @ w["w_down"].T + w["b_down"], 0) @ w["w_up"].T + w["b_up"]),
+    "adapter_no_relu": ("adapter_block", lambda x, w: (x @ w["w_down"].T + w["b_down"]) @ w["w_up"].T + w["b_up"] + x),
     "softmax_cols": ("softmax_rows", lambda s: np.exp(s - s.max()) / np.exp(s - s.max()).sum(0, keepdims=True)),
 }
 
@@ -457,6 +516,8 @@ def test_planted_mistake_in_the_oracle_is_caught(name, monkeypatch):
     pins = [lambda: test_encoder_postln_matches_torch_library_layer(7),
             lambda: test_decoder_preln_matches_torch_library_layer_with_causal_mask(7),
             lambda: test_ffn_block_hand_worked(),
+            lambda: test_adapter_block_hand_worked(),
+            lambda: test_shared_layer_with_adapter_hand_worked(),
             lambda: test_layer_norm_hand_and_moments(),
             lambda: test_gelu_closed_forms(),
             lambda: test_softmax_rows_hand(),
