@@ -38,7 +38,7 @@ def linear_flops_per_token(wl) -> float:
     d, f = wl.d_model, wl.d_ff
     if wl.block in (synth.BLOCK_FFN, synth.BLOCK_ADAPTER):
         return 4.0 * d * f
-    return 2.0 * (4 * d * d + 2 * d * f)
+    return 2.0 * (4 * d * d + 2 * d * f) + 4.0 * d * wl.adapter_rank
 
 
 def main() -> int:

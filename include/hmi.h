@@ -52,10 +52,15 @@ enum { HMI_F32 = 0, HMI_BF16 = 1 };
  *   DEC_PRELN   same tensors;  X1 = X + Attn(LN1(X));  Y = X1 + FFN(LN2(X1));  causal attention
  *   ADAPTER     w_down[r,d] b_down[r] w_up[d,r] b_up[d]   (r = d_ff)
  *               Y = X + Up(ReLU(Down(X)))                 (the paper's adapter, Sec. 3.2.2)
+ *   ENC_ADAPTER the paper's task-adapted higher layer (Sec. 3.2.2): one ENC_POSTLN tensor set per
+ *               layer shared by all tenants (hmi_pool_load_shared), and per tenant the ADAPTER
+ *               tensors with r = adapter_rank, injected after the attention layer:
+ *               A = Attn(X);  X1 = LN1(X + A + Up_t(ReLU(Down_t(A))));  Y = LN2(X1 + FFN(X1))
  * Attention is per request (never across requests), softmax scale 1/sqrt(d/n_heads),
  * packed qkv in q,k,v order, head h owns columns [h*d_head,(h+1)*d_head).  GELU is the
  * exact erf form; LayerNorm uses the biased variance and ln_eps inside the square root. */
-enum { HMI_BLOCK_FFN = 0, HMI_BLOCK_ENC_POSTLN = 1, HMI_BLOCK_DEC_PRELN = 2, HMI_BLOCK_ADAPTER = 3 };
+enum { HMI_BLOCK_FFN = 0, HMI_BLOCK_ENC_POSTLN = 1, HMI_BLOCK_DEC_PRELN = 2, HMI_BLOCK_ADAPTER = 3,
+       HMI_BLOCK_ENC_ADAPTER = 4 };
 
 typedef struct {
   int32_t block;        /* HMI_BLOCK_*                                                    */
@@ -73,6 +78,8 @@ typedef struct {
   float   ln_eps;
   int32_t device;       /* HIP device ordinal                                             */
   void*   compute_stream; /* hipStream_t borrowed from the caller; NULL = default stream  */
+  int32_t adapter_rank; /* ENC_ADAPTER: bottleneck width r of the per-tenant adapter, multiple
+                           of 64 (bf16) / 16 (f32), <= d_ff; ignored by the other blocks      */
 } hmi_pool_config_t;
 
 /* Create a pool (Sec. 4.1 "create hPLM" needs somewhere to put instances).  Allocates the
@@ -91,6 +98,14 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out);
 int32_t hmi_pool_load_tenant(hmi_pool_t* pool, int32_t tenant_id, int32_t layer,
                              const void* const* tensors, int32_t n_tensors);
 
+/* ENC_ADAPTER pools: register the parameters of `layer` that every tenant shares (the
+ * higher transformer layers stay on the GPU and are reused across tenants, Sec. 3.2.2).
+ * `tensors`: HOST array of the 12 ENC_POSTLN tensors as HOST pointers, pool dtype, dense
+ * row-major; copied to HBM before return.  Waits for work in flight when it replaces a
+ * layer that was loaded before.  Other block kinds: HMI_ERR_ARG. */
+int32_t hmi_pool_load_shared(hmi_pool_t* pool, int32_t layer, const void* const* tensors,
+                             int32_t n_tensors);
+
 /* The hot path (Sec. 6.3): y[rows of request r] = block_{tenant_ids[r]}(x[rows of request r]).
  * x, y: DEVICE, [N, d_model] packed in request order (request r owns rows
  * tok_off[r] .. tok_off[r]+seq_lens[r]), pool dtype, x != y, x is not modified.
@@ -98,7 +113,8 @@ int32_t hmi_pool_load_tenant(hmi_pool_t* pool, int32_t tenant_id, int32_t layer,
  * Work is enqueued on compute_stream and the call returns without waiting for it.
  * Errors are detected before anything is enqueued, so y is untouched on error:
  * unknown / unloaded tenant -> HMI_ERR_TENANT; seq_len <= 0, R or N over the configured
- * bound -> HMI_ERR_SHAPE; more distinct tenants than hbm_slots -> HMI_ERR_CAPACITY.
+ * bound -> HMI_ERR_SHAPE; more distinct tenants than hbm_slots -> HMI_ERR_CAPACITY;
+ * ENC_ADAPTER with the layer's shared parameters not loaded -> HMI_ERR_ARG.
  * n_requests == 0 is HMI_OK and does nothing. */
 int32_t hmi_layer_forward(hmi_pool_t* pool, int32_t layer, const void* x, void* y,
                           const int32_t* tenant_ids, const int32_t* seq_lens,

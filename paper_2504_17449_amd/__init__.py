@@ -19,9 +19,9 @@ LIB_PATH = os.environ.get("HMI_LIB_PATH") or os.path.join(_HERE, "libhmi.so")  #
 HMI_OK, HMI_ERR_ARG, HMI_ERR_OOM, HMI_ERR_TENANT, HMI_ERR_SHAPE, HMI_ERR_CAPACITY, HMI_ERR_DEVICE = \
     0, -1, -2, -3, -4, -5, -6
 HMI_F32, HMI_BF16 = 0, 1
-HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER = 0, 1, 2, 3
+HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER = 0, 1, 2, 3, 4
 
-EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_layer_forward", "hmi_stack_forward",
+EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_layer_forward", "hmi_stack_forward",
            "hmi_get_route",
            "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
            "hmi_pool_destroy"]
@@ -32,7 +32,7 @@ class hmi_pool_config_t(C.Structure):
                 ("d_ff", C.c_int32), ("n_heads", C.c_int32), ("n_layers", C.c_int32),
                 ("max_tenants", C.c_int32), ("hbm_slots", C.c_int32), ("host_tier", C.c_int32),
                 ("max_requests", C.c_int32), ("max_tokens", C.c_int32), ("ln_eps", C.c_float),
-                ("device", C.c_int32), ("compute_stream", C.c_void_p)]
+                ("device", C.c_int32), ("compute_stream", C.c_void_p), ("adapter_rank", C.c_int32)]
 
 
 class HmiError(RuntimeError):
@@ -52,6 +52,8 @@ def _load() -> C.CDLL:
     lib.hmi_pool_create.restype = i32
     lib.hmi_pool_load_tenant.argtypes = [vp, i32, i32, C.POINTER(vp), i32]
     lib.hmi_pool_load_tenant.restype = i32
+    lib.hmi_pool_load_shared.argtypes = [vp, i32, C.POINTER(vp), i32]
+    lib.hmi_pool_load_shared.restype = i32
     lib.hmi_layer_forward.argtypes = [vp, i32, vp, vp, pi32, pi32, i32]
     lib.hmi_layer_forward.restype = i32
     lib.hmi_stack_forward.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
@@ -95,12 +97,12 @@ def hmi_last_error(pool: Optional[int]) -> str:
 def hmi_pool_create(*, block: int, dtype: int, d_model: int, d_ff: int, n_heads: int = 0,
                     n_layers: int = 1, max_tenants: int, hbm_slots: Optional[int] = None,
                     host_tier: bool = False, max_requests: int, max_tokens: int,
-                    ln_eps: float = 1e-12, device: int = 0, compute_stream: int = 0):
+                    ln_eps: float = 1e-12, device: int = 0, compute_stream: int = 0, adapter_rank: int = 0):
     """-> (status, pool handle or None).  compute_stream: raw hipStream_t (torch's
     ``torch.cuda.current_stream().cuda_stream``), 0 = default stream."""
     cfg = hmi_pool_config_t(block, dtype, d_model, d_ff, n_heads, n_layers, max_tenants,
                             max_tenants if hbm_slots is None else hbm_slots, int(host_tier),
-                            max_requests, max_tokens, ln_eps, device, compute_stream or None)
+                            max_requests, max_tokens, ln_eps, device, compute_stream or None, adapter_rank)
     out = C.c_void_p()
     rc = lib.hmi_pool_create(C.byref(cfg), C.byref(out))
     return rc, (out.value if rc == HMI_OK else None)
@@ -112,6 +114,13 @@ def hmi_pool_load_tenant(pool: int, tenant_id: int, layer: int, tensors: Sequenc
     keep = [np.ascontiguousarray(t) for t in tensors]
     arr = (C.c_void_p * len(keep))(*[t.ctypes.data for t in keep])
     return lib.hmi_pool_load_tenant(pool, tenant_id, layer, arr, len(keep))
+
+
+def hmi_pool_load_shared(pool: int, layer: int, tensors: Sequence[np.ndarray]) -> int:
+    """tensors: the shared layer's host arrays in canonical order, pool storage dtype."""
+    keep = [np.ascontiguousarray(t) for t in tensors]
+    arr = (C.c_void_p * len(keep))(*[t.ctypes.data for t in keep])
+    return lib.hmi_pool_load_shared(pool, layer, arr, len(keep))
 
 
 def hmi_layer_forward(pool: int, layer: int, x_ptr: int, y_ptr: int, tenant_ids, seq_lens) -> int:
@@ -195,6 +204,9 @@ class Pool:
 
     def load_tenant(self, tenant_id: int, layer: int, tensors) -> None:
         self._check(hmi_pool_load_tenant(self.h, tenant_id, layer, tensors))
+
+    def load_shared(self, layer: int, tensors) -> None:
+        self._check(hmi_pool_load_shared(self.h, layer, tensors))
 
     def forward(self, layer: int, x, y, tenant_ids, seq_lens) -> None:
         """x, y: torch tensors on the pool's device ([N, d], pool dtype, contiguous)."""

@@ -8,6 +8,7 @@ namespace hmi {
 
 constexpr int kRouterThreads = 1024;
 constexpr int kMaxRequests = 2048;   // router keeps keys/values of one batch in LDS
+constexpr int kDenseSegRows = 1024;  // rows per pseudo-segment of the route for shared parameters
 
 // Output of the tenant-segmented router, all DEVICE int32 arrays.
 struct Route {
@@ -31,6 +32,12 @@ struct Route {
   // scratch of the persistent GEMM: per XCD a tile-claim counter [0..7] and a count of finished
   // workgroups [8..15], then one mailbox per workgroup; all zero between launches
   int32_t* gemm_sched;
+  // Written by the router when not null: the segment offsets of a second route over the same
+  // N rows for parameters that all tenants share.  That route takes the rows in their
+  // original order and cuts them into pseudo-segments of kDenseSegRows rows (the last one
+  // shorter), which all name slot 0; its tile lists and row map do not depend on the batch.
+  int32_t* dense_seg_tok_off;   // [ceil(N / kDenseSegRows) + 1]
+  int32_t* dense_n_segments;    // [1]
 };
 constexpr int kGemmSchedInts = 16 + 1024;
 
@@ -90,6 +97,7 @@ void pack_adapter_operand(void* dst, const void* src, int rows, int cols);
 // out_st (storage dtype, may be null).  All [N, d] in original packed order.
 struct LnArgs {
   const void* in; int in_f32;
+  const void* in2;                    // optional second addend in the storage dtype: LN(in + in2)
   float* out_f32; void* out_st;
   const char* pool; size_t slot_stride; size_t g_off, b_off;
   int d; float eps; int n_rows; int bf16;

@@ -3,6 +3,7 @@
 // found by a binary search of the row's sorted position in the segment token offsets.
 // Used after the residual adds of the per-tenant blocks (post-LN) or before the
 // sub-layers (pre-LN); the paper leaves these to BERT / GPT's layer definitions.
+// An optional second input is added first (residual stream + adapted attention output).
 #include "hmi_kernels.h"
 
 namespace hmi {
@@ -43,6 +44,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a, Route rt) {
       if (a.in_f32) v[i] = reinterpret_cast<const float*>(a.in)[idx];
       else v[i] = BF16 ? bf2f(reinterpret_cast<const uint16_t*>(a.in)[idx])
                        : reinterpret_cast<const float*>(a.in)[idx];
+      if (a.in2) v[i] += BF16 ? bf2f(reinterpret_cast<const uint16_t*>(a.in2)[idx])
+                              : reinterpret_cast<const float*>(a.in2)[idx];
       s += v[i];
     }
   }
@@ -104,6 +107,10 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) 
   f32x4 v[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) v[i] = load4(a.in, row * d + i * 256 + lane * 4, in_f32);
+  if (a.in2) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] += load4(a.in2, row * d + i * 256 + lane * 4, !BF16);
+  }
   const int G = rt.n_segments[0];
   for (int i = threadIdx.x; i <= G; i += 256) seg_s[i] = rt.seg_tok_off[i];
   __syncthreads();

@@ -101,7 +101,15 @@ struct hmi_pool {
   Route rt{};
   int last_R = 0;
   int tile_m[2] = {256, 128};
-  bool adapter_fused = false;  // single-layer bf16 adapter pool: matrices kept in operand order, one kernel
+  bool adapter_fused = false;  // bf16 adapter images keep their matrices in operand order, one kernel
+  int rank = 0;                // adapter bottleneck width (ADAPTER: d_ff, ENC_ADAPTER: adapter_rank)
+
+  // parameters shared by all tenants (ENC_ADAPTER): one encoder-layer image per layer
+  std::vector<TensorLoc> stl;
+  size_t shared_image_bytes = 0;
+  char* d_shared = nullptr;
+  std::vector<uint8_t> shared_loaded;
+  Route rt_dense{};            // route for GEMMs / LayerNorms that read them
 
   // workspaces
   char *w_qkv = nullptr, *w_ctx = nullptr, *w_hmid = nullptr, *w_act = nullptr;
@@ -156,8 +164,20 @@ std::vector<std::pair<int64_t, int64_t>> tensor_shapes(const hmi_pool_config_t& 
       out.push_back({d, 0}); out.push_back({d, 0}); break;
     case HMI_BLOCK_ADAPTER:
       out = ffn; break;
+    case HMI_BLOCK_ENC_ADAPTER: {
+      const int64_t r = c.adapter_rank;
+      out = {{r, d}, {r, 0}, {d, r}, {d, 0}}; break;
+    }
   }
   return out;
+}
+
+// Tensors of the layer that all tenants of an ENC_ADAPTER pool share: an ENC_POSTLN set.
+std::vector<std::pair<int64_t, int64_t>> shared_tensor_shapes(const hmi_pool_config_t& c) {
+  if (c.block != HMI_BLOCK_ENC_ADAPTER) return {};
+  hmi_pool_config_t e = c;
+  e.block = HMI_BLOCK_ENC_POSTLN;
+  return tensor_shapes(e);
 }
 
 enum { T_W1 = 0, T_B1, T_W2, T_B2, T_LNG, T_LNB };                      // FFN / ADAPTER
@@ -167,6 +187,7 @@ void free_all(hmi_pool* p) {
   (void)hipStreamSynchronize(p->compute);
   if (p->copy) (void)hipStreamSynchronize(p->copy);
   (void)hipFree(p->d_pool);
+  (void)hipFree(p->d_shared);
   (void)hipFree(p->d_idx);
   (void)hipFree(p->w_qkv); (void)hipFree(p->w_ctx); (void)hipFree(p->w_hmid);
   (void)hipFree(p->w_act); (void)hipFree(p->w_z); (void)hipFree(p->w_x1);
@@ -255,8 +276,8 @@ struct ProfSpan {
 // Writes one (tenant, layer) image from the caller's canonical tensors.
 void write_image(const hmi_pool* p, char* img, const void* const* tensors) {
   for (size_t i = 0; i < p->tl.size(); ++i) {
-    if (p->adapter_fused && i == T_W1) pack_adapter_operand(img + p->tl[i].off, tensors[i], p->cfg.d_ff, p->cfg.d_model);
-    else if (p->adapter_fused && i == T_W2) pack_adapter_operand(img + p->tl[i].off, tensors[i], p->cfg.d_model, p->cfg.d_ff);
+    if (p->adapter_fused && i == T_W1) pack_adapter_operand(img + p->tl[i].off, tensors[i], p->rank, p->cfg.d_model);
+    else if (p->adapter_fused && i == T_W2) pack_adapter_operand(img + p->tl[i].off, tensors[i], p->cfg.d_model, p->rank);
     else memcpy(img + p->tl[i].off, tensors[i], p->tl[i].bytes);
   }
 }
@@ -274,12 +295,18 @@ extern "C" {
 int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   if (!cfg || !out) return fail(nullptr, HMI_ERR_ARG, "null config or out pointer");
   const hmi_pool_config_t& c = *cfg;
-  if (c.block < HMI_BLOCK_FFN || c.block > HMI_BLOCK_ADAPTER) return fail(nullptr, HMI_ERR_ARG, "bad block %d", c.block);
+  if (c.block < HMI_BLOCK_FFN || c.block > HMI_BLOCK_ENC_ADAPTER) return fail(nullptr, HMI_ERR_ARG, "bad block %d", c.block);
   if (c.dtype != HMI_F32 && c.dtype != HMI_BF16) return fail(nullptr, HMI_ERR_ARG, "bad dtype %d", c.dtype);
   const int mult = c.dtype == HMI_BF16 ? 64 : 16;
   if (c.d_model <= 0 || c.d_ff <= 0 || c.d_model % mult || c.d_ff % mult || c.d_model > 2048)
     return fail(nullptr, HMI_ERR_ARG, "d_model/d_ff must be positive multiples of %d (d_model <= 2048)", mult);
-  const bool attn = c.block == HMI_BLOCK_ENC_POSTLN || c.block == HMI_BLOCK_DEC_PRELN;
+  const bool attn = c.block == HMI_BLOCK_ENC_POSTLN || c.block == HMI_BLOCK_DEC_PRELN || c.block == HMI_BLOCK_ENC_ADAPTER;
+  if (c.block == HMI_BLOCK_ENC_ADAPTER) {
+    if (c.adapter_rank <= 0 || c.adapter_rank % mult || c.adapter_rank > c.d_ff)
+      return fail(nullptr, HMI_ERR_ARG, "adapter_rank must be a positive multiple of %d and <= d_ff", mult);
+    if ((int64_t)c.max_tokens > (int64_t)kMaxRequests * kDenseSegRows)
+      return fail(nullptr, HMI_ERR_ARG, "max_tokens must be <= %d for this block", kMaxRequests * kDenseSegRows);
+  }
   if (attn) {
     if (c.n_heads <= 0 || c.d_model % c.n_heads) return fail(nullptr, HMI_ERR_ARG, "n_heads must divide d_model");
     const int dh = c.d_model / c.n_heads;
@@ -300,7 +327,11 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   p->esize = p->bf16 ? 2 : 4;
   p->tile_m[0] = p->bf16 ? kBf16TileM0 : kF32TileM;
   p->tile_m[1] = p->bf16 ? kBf16TileM1 : 0;
-  p->adapter_fused = p->bf16 && c.block == HMI_BLOCK_ADAPTER && c.n_layers == 1 && adapter_bf16_supported(c.d_model, c.d_ff);
+  p->rank = c.block == HMI_BLOCK_ENC_ADAPTER ? c.adapter_rank : c.d_ff;
+  // The one-kernel adapter reads and writes the storage dtype: inside the shared layer it always
+  // can, as a block of its own only where no fp32 activations pass between layers.
+  p->adapter_fused = p->bf16 && adapter_bf16_supported(c.d_model, p->rank) &&
+                     (c.block == HMI_BLOCK_ENC_ADAPTER || (c.block == HMI_BLOCK_ADAPTER && c.n_layers == 1));
   size_t off = 0;
   for (auto& sh : tensor_shapes(c)) {
     const size_t bytes = (size_t)sh.first * (sh.second ? sh.second : 1) * p->esize;
@@ -309,6 +340,14 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   }
   p->image_bytes = off;
   p->slot_stride = off * c.n_layers;
+  off = 0;
+  for (auto& sh : shared_tensor_shapes(c)) {
+    const size_t bytes = (size_t)sh.first * (sh.second ? sh.second : 1) * p->esize;
+    p->stl.push_back({off, bytes});
+    off = align_up(off + bytes, kAlign);
+  }
+  p->shared_image_bytes = off;
+  p->shared_loaded.assign(c.n_layers, 0);
 
 #define CREATE_TRY(call)                                                                        \
   do {                                                                                          \
@@ -329,6 +368,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
     return fail(nullptr, HMI_ERR_DEVICE, "event creation failed");
   }
   CREATE_TRY(hipMalloc(&p->d_pool, p->slot_stride * (size_t)c.hbm_slots));
+  if (p->shared_image_bytes) CREATE_TRY(hipMalloc(&p->d_shared, p->shared_image_bytes * (size_t)c.n_layers));
 
   p->slot_of_tenant.assign(c.max_tenants, -1);
   p->tenant_of_slot.assign(c.hbm_slots, -1);
@@ -365,6 +405,10 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
                  + MT                      // row_src
                  + 2 * (max_tiles0 + max_tiles1) + 4   // tile lists + counters
                  + kGemmSchedInts;
+  const bool dense = c.block == HMI_BLOCK_ENC_ADAPTER;
+  const size_t dense_segs = MT / kDenseSegRows + 2;
+  const size_t dense_tiles0 = MT / p->tile_m[0] + 2, dense_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + 2 : 0;
+  if (dense) n_i32 += 2 * dense_segs + 1 + MT + 2 * (dense_tiles0 + dense_tiles1);
   CREATE_TRY(hipMalloc(&p->d_idx, n_i32 * sizeof(int32_t)));
   CREATE_TRY(hipMemset(p->d_idx, 0, n_i32 * sizeof(int32_t)));
   int32_t* q = p->d_idx;
@@ -382,6 +426,36 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   rt.gemm_sched = take(kGemmSchedInts);
   rt.tile_m[0] = p->tile_m[0]; rt.tile_m[1] = p->tile_m[1];
   rt.key_bits = bits_for(c.max_tenants);
+  if (dense) {
+    // Route for the shared parameters: identity row map, pseudo-segments of kDenseSegRows rows
+    // that all name slot 0 (the GEMMs get a slot stride of 0), tiles in row order.  Only the
+    // segment offsets depend on the batch (its N); the router writes them.
+    Route& rd = p->rt_dense;
+    rd = rt;
+    rd.seg_slot = take(dense_segs);            // stays zero
+    rd.seg_tok_off = take(dense_segs);
+    rd.n_segments = take(1);
+    rd.row_src = take(MT);
+    rd.tile_seg[0] = take(dense_tiles0); rd.tile_row0[0] = take(dense_tiles0);
+    rd.tile_seg[1] = dense_tiles1 ? take(dense_tiles1) : nullptr;
+    rd.tile_row0[1] = dense_tiles1 ? take(dense_tiles1) : nullptr;
+    rt.dense_seg_tok_off = rd.seg_tok_off;
+    rt.dense_n_segments = rd.n_segments;
+    std::vector<int32_t> h(MT);
+    for (size_t i = 0; i < MT; ++i) h[i] = (int32_t)i;
+    CREATE_TRY(hipMemcpy(rd.row_src, h.data(), MT * sizeof(int32_t), hipMemcpyHostToDevice));
+    for (int k = 0; k < 2; ++k) {
+      const size_t nt = k == 0 ? dense_tiles0 : dense_tiles1;
+      if (!nt) continue;
+      std::vector<int32_t> seg(nt), row0(nt);
+      for (size_t t = 0; t < nt; ++t) {
+        row0[t] = (int32_t)(t * p->tile_m[k]);
+        seg[t] = (int32_t)(t * p->tile_m[k] / kDenseSegRows);
+      }
+      CREATE_TRY(hipMemcpy(rd.tile_seg[k], seg.data(), nt * sizeof(int32_t), hipMemcpyHostToDevice));
+      CREATE_TRY(hipMemcpy(rd.tile_row0[k], row0.data(), nt * sizeof(int32_t), hipMemcpyHostToDevice));
+    }
+  }
 
   const size_t d = c.d_model, f = c.d_ff, es = p->esize;
   CREATE_TRY(hipMalloc(&p->w_hmid, MT * f * es));
@@ -468,6 +542,28 @@ int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
   return HMI_OK;
 }
 
+int32_t hmi_pool_load_shared(hmi_pool_t* p, int32_t layer, const void* const* tensors, int32_t n_tensors) {
+  if (!p) return HMI_ERR_ARG;
+  if (p->cfg.block != HMI_BLOCK_ENC_ADAPTER) return fail(p, HMI_ERR_ARG, "this block kind has no shared parameters");
+  if (!tensors) return fail(p, HMI_ERR_ARG, "null tensor list");
+  if (layer < 0 || layer >= p->cfg.n_layers) return fail(p, HMI_ERR_ARG, "layer %d outside [0,%d)", layer, p->cfg.n_layers);
+  if (n_tensors != (int32_t)p->stl.size()) return fail(p, HMI_ERR_SHAPE, "the shared layer has %d tensors, got %d", (int)p->stl.size(), n_tensors);
+  for (int i = 0; i < n_tensors; ++i)
+    if (!tensors[i]) return fail(p, HMI_ERR_ARG, "tensor %d is null", i);
+  HIP_TRY(p, hipSetDevice(p->cfg.device));
+  if (p->shared_loaded[layer]) HIP_TRY(p, hipStreamSynchronize(p->compute));   // may still be read
+  char* stage = nullptr;
+  HIP_TRY(p, hipHostMalloc(&stage, p->shared_image_bytes, hipHostMallocDefault));
+  for (int i = 0; i < n_tensors; ++i) memcpy(stage + p->stl[i].off, tensors[i], p->stl[i].bytes);
+  hipError_t e = hipMemcpyAsync(p->d_shared + (size_t)layer * p->shared_image_bytes, stage, p->shared_image_bytes,
+                                hipMemcpyHostToDevice, p->copy);
+  if (e == hipSuccess) e = hipStreamSynchronize(p->copy);   // in HBM before return: later forwards need no event
+  (void)hipHostFree(stage);
+  if (e != hipSuccess) return fail(p, HMI_ERR_DEVICE, "copy of the shared layer failed: %s", hipGetErrorString(e));
+  p->shared_loaded[layer] = 1;
+  return HMI_OK;
+}
+
 int32_t hmi_pool_prefetch(hmi_pool_t* p, int32_t layer, const int32_t* ids, int32_t n) {
   if (!p) return HMI_ERR_ARG;
   if (n < 0 || (n > 0 && !ids)) return fail(p, HMI_ERR_ARG, "bad tenant list");
@@ -515,6 +611,9 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
   if (R > p->cfg.max_requests) return fail(p, HMI_ERR_SHAPE, "%d requests > max_requests %d", R, p->cfg.max_requests);
   const hmi_pool_config_t& c = p->cfg;
   const int L = c.n_layers;
+  if (c.block == HMI_BLOCK_ENC_ADAPTER)
+    for (int l = layer_begin; l < layer_end; ++l)
+      if (!p->shared_loaded[l]) return fail(p, HMI_ERR_ARG, "shared parameters of layer %d were never loaded", l);
 
   // ---- validate, count tokens per distinct tenant
   if (++p->epoch == 0) { std::fill(p->mark.begin(), p->mark.end(), 0u); p->epoch = 1; }
@@ -644,6 +743,31 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
       ProfSpan ps(p, HMI_KERNEL_LAYERNORM);
       launch_layernorm(a, rt, s);
     };
+    // the same two with the parameters all tenants share: slot stride 0, dense route
+    const size_t slay = (size_t)layer * p->shared_image_bytes;
+    auto sgemm = [&](const void* A, int lda, int tw, int tb, int n_out, int k, int epi, void* C, int ldc,
+                     const void* resid, int ldr, bool resid_f32, bool out_f32) {
+      GemmArgs g{};
+      g.A = A; g.lda = lda; g.C = C; g.ldc = ldc; g.resid = resid; g.ldr = ldr;
+      g.resid_f32 = resid_f32; g.out_f32 = out_f32; g.C2 = nullptr;
+      g.pool = p->d_shared; g.slot_stride = 0;
+      g.w_off = slay + p->stl[tw].off; g.b_off = slay + p->stl[tb].off;
+      g.n_out = n_out; g.k = k; g.epi = epi;
+      g.n_mtiles_list[0] = (int)((N + p->tile_m[0] - 1) / p->tile_m[0]);
+      g.n_mtiles_list[1] = p->tile_m[1] ? (int)((N + p->tile_m[1] - 1) / p->tile_m[1]) : 0;
+      g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
+      ProfSpan ps(p, HMI_KERNEL_GEMM);
+      if (p->bf16) launch_gemm_bf16(g, p->rt_dense, s); else launch_gemm_f32(g, p->rt_dense, s);
+    };
+    auto slnorm = [&](const void* in, bool in_f32, const void* in2, float* out_f32, void* out_st, int tg, int tb) {
+      LnArgs a{};
+      a.in = in; a.in_f32 = in_f32; a.in2 = in2; a.out_f32 = out_f32; a.out_st = out_st;
+      a.pool = p->d_shared; a.slot_stride = 0;
+      a.g_off = slay + p->stl[tg].off; a.b_off = slay + p->stl[tb].off;
+      a.d = d; a.eps = c.ln_eps; a.n_rows = (int)N; a.bf16 = p->bf16;
+      ProfSpan ps(p, HMI_KERNEL_LAYERNORM);
+      launch_layernorm(a, p->rt_dense, s);
+    };
     auto attention = [&](bool causal) {
       AttnArgs a{};
       a.qkv = p->w_qkv; a.ctx = p->w_ctx; a.d = d; a.n_heads = c.n_heads; a.causal = causal;
@@ -685,6 +809,32 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
         gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_z, d, p->w_x1, d, true, true, nullptr);
         lnorm(p->w_z, true, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, A_LN2G, A_LN2B);
         break;
+      case HMI_BLOCK_ENC_ADAPTER: {
+        // the shared layer with the tenant's adapter after the attention layer (Sec. 3.2.2):
+        // only the adapter step reads per-tenant parameters and follows the tenant route
+        const int r = p->rank;
+        sgemm(in_st, d, A_WQKV, A_BQKV, 3 * d, d, EPI_BIAS, p->w_qkv, 3 * d, nullptr, 0, false, false);
+        attention(false);
+        sgemm(p->w_ctx, d, A_WO, A_BO, d, d, EPI_BIAS, p->w_act, d, nullptr, 0, false, false);
+        if (p->adapter_fused) {
+          AdapterArgs a{};
+          a.X = p->w_act; a.Y = p->w_ctx; a.pool = p->d_pool; a.slot_stride = p->slot_stride;
+          a.wd_off = lay + p->tl[T_W1].off; a.bd_off = lay + p->tl[T_B1].off;
+          a.wu_off = lay + p->tl[T_W2].off; a.bu_off = lay + p->tl[T_B2].off;
+          a.d = d; a.which_tiles = 1; a.n_tiles128 = n_mtiles[1];
+          ProfSpan ps(p, HMI_KERNEL_GEMM);
+          launch_adapter_bf16(a, rt, s);
+        } else {
+          gemm(p->w_act, d, T_W1, T_B1, r, d, EPI_BIAS_RELU, p->w_hmid, r, nullptr, 0, false, false, nullptr);
+          gemm(p->w_hmid, r, T_W2, T_B2, d, r, EPI_BIAS_RESID, p->w_ctx, d, p->w_act, d, f32, f32, nullptr);
+        }
+        slnorm(in_res, in_res_f32, p->w_ctx, p->w_x1, p->bf16 ? p->w_act : nullptr, A_LN1G, A_LN1B);
+        sgemm(p->bf16 ? (const void*)p->w_act : (const void*)p->w_x1, d, A_W1, A_B1, f, d, EPI_BIAS_GELU,
+              p->w_hmid, f, nullptr, 0, false, false);
+        sgemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_z, d, p->w_x1, d, true, true);
+        slnorm(p->w_z, true, nullptr, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, A_LN2G, A_LN2B);
+        break;
+      }
       case HMI_BLOCK_DEC_PRELN:
         lnorm(in_res, in_res_f32, nullptr, p->w_act, A_LN1G, A_LN1B);
         gemm(p->w_act, d, A_WQKV, A_BQKV, 3 * d, d, EPI_BIAS, p->w_qkv, 3 * d, nullptr, 0, false, false, nullptr);

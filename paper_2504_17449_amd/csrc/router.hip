@@ -79,6 +79,11 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
   }
   const int N = carry;
   if (tid == 0) { tok_s[R] = N; rt.tok_off[R] = N; }
+  if (rt.dense_seg_tok_off) {
+    const int Gd = (N + kDenseSegRows - 1) / kDenseSegRows;
+    for (int g = tid; g <= Gd; g += kRouterThreads) rt.dense_seg_tok_off[g] = min(g * kDenseSegRows, N);
+    if (tid == 0) rt.dense_n_segments[0] = Gd;
+  }
   __syncthreads();
 
   // ---- stable LSD radix sort of (tenant id, request) by tenant id

@@ -72,6 +72,11 @@ def test_adapter_block_1000_tenants_full_size():
     run_full(synth.WORKLOADS["hbert_adapter"])
 
 
+def test_shared_layers_with_adapters_1000_tenants_full_size():
+    """The six shared higher layers with per-tenant adapters, as bench.py --workload hbert_shared_adapter runs them."""
+    run_full(synth.WORKLOADS["hbert_shared_adapter"], sample_kw=dict(n_multi=4, n_single=6))
+
+
 # ------------------------------------------------------------------ host tier
 
 class LruModel:

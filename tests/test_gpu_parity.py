@@ -57,6 +57,8 @@ def small(block, dtype, **kw):
     base.update(kw)
     if block in (synth.BLOCK_FFN, synth.BLOCK_ADAPTER):
         base["n_heads"] = 0
+    if block == synth.BLOCK_ENC_ADAPTER:
+        base.setdefault("adapter_rank", 64 if dtype == "bf16" else 16)
     return synth.Workload(**base)
 
 
@@ -65,27 +67,28 @@ def test_tiny_fp32_ffn_full_config(hmi):
 
 
 @pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
-                                   synth.BLOCK_ADAPTER])
+                                   synth.BLOCK_ADAPTER, synth.BLOCK_ENC_ADAPTER])
 def test_small_fp32_blocks_ragged(hmi, block):
     run_case(hmi, small(block, "f32", d_model=64, d_ff=128, n_heads=4, seq_max=90))
 
 
 @pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
-                                   synth.BLOCK_ADAPTER])
+                                   synth.BLOCK_ADAPTER, synth.BLOCK_ENC_ADAPTER])
 def test_small_bf16_blocks_ragged(hmi, block):
     # seq up to 300: m-tiles of 256 rows with ragged tails, several key blocks, q blocks
     run_case(hmi, small(block, "bf16"))
 
 
 @pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
-                                   synth.BLOCK_ADAPTER])
+                                   synth.BLOCK_ADAPTER, synth.BLOCK_ENC_ADAPTER])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_layer_stack_in_one_call(hmi, block, dtype):
     kw = dict(d_model=64, d_ff=128, n_heads=4) if dtype == "f32" else {}
     run_case(hmi, small(block, dtype, n_layers=3, seq_max=140, **kw))
 
 
-@pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN])
+@pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
+                                   synth.BLOCK_ENC_ADAPTER])
 def test_wide_bf16_blocks_ragged_every_row(hmi, block):
     """Widths that are multiples of 256 with k >= 192 take the persistent 256 x 256 GEMM: ragged
     segments of 1..300 rows (short tiles, clamped rows, several tiles per segment), every output
@@ -180,6 +183,60 @@ def test_fused_adapter_ragged_large_weights(hmi, d_model):
     assert ok, (max_abs, rel)
     y2_ref = O.layer_forward(synth.BLOCK_ADAPTER, X[:N2].astype(np.float64), ids2, lens2, get, 0, 0.0)
     max_abs, rel, ok = compare(y2_gpu, y2_ref, np.arange(N2), "bf16")
+    assert ok, (max_abs, rel)
+
+
+def test_shared_layer_with_loud_adapters(hmi):
+    """The paper's task-adapted layer (shared encoder layer, tenant adapter after the attention
+    layer) with adapters loud enough to matter: with the seeded recipe's N(0, 0.02) adapter
+    weights a wrong or missing adapter would hide inside the tolerance, here the adapter's
+    output is larger than the attention output it is added to (LayerNorm gains near 0.6 keep |y|
+    below 4, where a bf16 half-ulp is still under the max-abs tolerance).  d = 256 takes the one-kernel
+    adapter inside the layer; two layers in one call; every row compared."""
+    from paper_2504_17449_amd import harness
+    rng = np.random.default_rng(77)
+    T, R, d, f, r, h, L = 12, 30, 256, 512, 64, 4, 2
+    wl = small(synth.BLOCK_ENC_ADAPTER, "bf16", d_model=d, d_ff=f, n_heads=h, n_layers=L, n_tenants=T,
+               hbm_slots=T, n_requests=R, adapter_rank=r, ln_eps=1e-5)
+    ids = rng.integers(0, T, R).astype(np.int32)
+    lens = rng.integers(1, 151, R).astype(np.int32)
+    N = int(lens.sum())
+    rb = lambda a: synth.round_to_storage(np.asarray(a, dtype=np.float32), "bf16")
+    n = lambda sc, *s: rb(rng.normal(0, sc, s))
+    shared = [{"wqkv": n(0.05, 3 * d, d), "bqkv": n(0.05, 3 * d), "wo": n(0.05, d, d), "bo": n(0.05, d),
+               "ln1_g": rb(0.6 + rng.normal(0, 0.05, d)), "ln1_b": n(0.1, d), "w1": n(0.05, f, d), "b1": n(0.05, f),
+               "w2": n(0.05, d, f), "b2": n(0.05, d), "ln2_g": rb(0.6 + rng.normal(0, 0.05, d)), "ln2_b": n(0.1, d)}
+              for _ in range(L)]
+    adapters = {(t, l): {"w_down": n(0.2, r, d), "b_down": n(0.2, r), "w_up": n(0.2, d, r), "b_up": n(0.2, d)}
+                for t in sorted(set(ids.tolist())) for l in range(L)}
+    X = rb(rng.normal(0, 1.0, (N, d)))
+    raw = lambda a: synth.to_storage_bytes(a, "bf16")
+    pool = harness.create_pool(wl, max_requests=R, max_tokens=N)
+    try:
+        for l in range(L):
+            pool.load_shared(l, [raw(shared[l][k]) for k, _, _ in synth.shared_specs(wl)])
+        for (t, l), w in adapters.items():
+            pool.load_tenant(t, l, [raw(w[k]) for k in ("w_down", "b_down", "w_up", "b_up")])
+        x = harness.host_to_device(X, "bf16")
+        y = torch.empty_like(x)
+        pool.stack_forward(0, L, x, y, ids, lens)
+        torch.cuda.synchronize()
+        check_route(pool, ids, lens)
+        y_gpu = harness.device_to_f64(y)
+    finally:
+        pool.close()
+    cur = X.astype(np.float64)
+    quiet = cur
+    for l in range(L):
+        full = lambda t, l=l: {**{k: v.astype(np.float64) for k, v in shared[l].items()},
+                               **{k: v.astype(np.float64) for k, v in adapters[(t, l)].items()}}
+        cur = O.layer_forward(synth.BLOCK_ENC_ADAPTER, cur, ids, lens, full, h, 1e-5)
+        mute = lambda t, l=l: {**full(t), "w_up": np.zeros((d, r)), "b_up": np.zeros(d)}
+        quiet = O.layer_forward(synth.BLOCK_ENC_ADAPTER, quiet, ids, lens, mute, h, 1e-5)
+    max_abs, rel, ok = compare(y_gpu, cur, np.arange(N), "bf16")
+    loud = np.linalg.norm(cur - quiet) / np.linalg.norm(cur)
+    print(f"  max_abs={max_abs:.3e} rel_fro={rel:.3e} max|y|={np.abs(cur).max():.2f} adapters move y by {loud:.2f}", flush=True)
+    assert loud > 0.3
     assert ok, (max_abs, rel)
 
 
