@@ -146,7 +146,7 @@ def main() -> int:
     if wl.block == synth.BLOCK_ADAPTER and bf16 and wl.n_layers == 1:
         # One fused kernel that moves 4 d bytes per token for 256 d flops per token: bound by HBM.
         # Algorithmic bytes: x in, y out, and each present tenant's image once.
-        algo_bytes = 2.0 * N * wl.d_model * 2 + len(set(ids.tolist())) * pool.image_bytes()
+        algo_bytes = 2.0 * N * wl.d_model * 2 + len(set(ids.tolist())) * pool.image_bytes
         gbs = algo_bytes / (gemm_launch_ms * 1e-3) / 1e9
         roofline.update({"bound": "hbm", "kernel": "adapter_fused", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
                          "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
