@@ -29,7 +29,8 @@ PEAK_HBM_GBS = 8000.0       # HBM3E, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by a copy kernel of known size in the same run, see --copy-calibration):
 # mean over the FFN1 and FFN2 launches, from profiles/gemm_bf16_p256_bert_ffn.md.
-MEASURED_TRAFFIC_BYTES = {"bert_ffn": 8.05e8}
+MEASURED_TRAFFIC_BYTES = {"bert_ffn": 8.05e8,
+                          "hbert_adapter": 2.609e8}   # profiles/adapter_bf16_hbert_adapter.md
 
 
 def linear_flops_per_token(wl) -> float:
@@ -149,7 +150,7 @@ def main() -> int:
         algo_bytes = 2.0 * N * wl.d_model * 2 + len(set(ids.tolist())) * pool.image_bytes
         gbs = algo_bytes / (gemm_launch_ms * 1e-3) / 1e9
         roofline.update({"bound": "hbm", "kernel": "adapter_fused", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
-                         "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                         "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
                          "bytes_per_launch": algo_bytes})
         del roofline["flop_per_launch"]
 
