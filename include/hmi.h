@@ -80,6 +80,8 @@ typedef struct {
   void*   compute_stream; /* hipStream_t borrowed from the caller; NULL = default stream  */
   int32_t adapter_rank; /* ENC_ADAPTER: bottleneck width r of the per-tenant adapter, multiple
                            of 64 (bf16) / 16 (f32), <= d_ff; ignored by the other blocks      */
+  int32_t max_classes;  /* > 0: tenants may own an output head with up to this many classes
+                           (<= 64), see hmi_pool_load_head; 0: no heads                        */
 } hmi_pool_config_t;
 
 /* Create a pool (Sec. 4.1 "create hPLM" needs somewhere to put instances).  Allocates the
@@ -130,6 +132,25 @@ int32_t hmi_layer_forward(hmi_pool_t* pool, int32_t layer, const void* x, void* 
 int32_t hmi_stack_forward(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_end,
                           const void* x, void* y, const int32_t* tenant_ids,
                           const int32_t* seq_lens, int32_t n_requests);
+
+/* Per-tenant output heads (Sec. 3.3.2): one linear layer per tenant on the final hidden states,
+ * with the tenant's own number of classes.  A classification tenant (per_token = 0) is scored on
+ * the first row of each of its requests (the [CLS] token at the beginning of the sentence), a
+ * tagging tenant (per_token = 1) on every row; the label is the class with the highest score
+ * (lowest index on ties).  w: HOST [n_classes, d_model] row-major, b: HOST [n_classes], pool
+ * dtype; copied to HBM before return (heads of all tenants stay resident: they are a few KB).
+ * 1 <= n_classes <= max_classes, else HMI_ERR_SHAPE. */
+int32_t hmi_pool_load_head(hmi_pool_t* pool, int32_t tenant_id, const void* w, const void* b,
+                           int32_t n_classes, int32_t per_token);
+
+/* Scores the batch of the most recent forward call on this pool (its tenant_ids and seq_lens;
+ * the routing it left on the device is reused) from h: DEVICE [N, d_model], pool dtype, normally
+ * that call's y.  scores: DEVICE float [N, max_classes] or NULL; labels: DEVICE int32 [N].
+ * Rows without a prediction (rows after the first of a classification tenant's request) get
+ * label -1 and scores -inf; columns at or beyond the tenant's class count get -inf.  Scores are
+ * accumulated and compared in fp32.  Enqueued on compute_stream.  No earlier forward call ->
+ * HMI_ERR_ARG; a tenant of that batch without a head -> HMI_ERR_TENANT (nothing enqueued). */
+int32_t hmi_head_forward(hmi_pool_t* pool, const void* h, float* scores, int32_t* labels);
 
 /* Routing of the last forward call, for bit-exact checks of the tenant-segmented router:
  * perm[R] (stable order of requests by tenant id), seg_tenant[G], seg_req_off[G+1],

@@ -200,3 +200,33 @@ def layer_forward(block: int, X: np.ndarray, tenant_ids: Sequence[int], seq_lens
             Y[start:start + S] = block_forward(block, X[start:start + S], w, n_heads, eps)
         start += S
     return Y
+
+
+# --------------------------------------------------------------------------- output heads
+
+def head_forward(H: np.ndarray, tenant_ids: Sequence[int], seq_lens: Sequence[int],
+                 head_of: Callable[[int], tuple], max_classes: int):
+    """Per-tenant output heads on the final hidden states H [N, d] (Sec. 3.3.2): every tenant
+    owns one linear layer (W [C, d], b [C]) with its own number of classes C.  A
+    classification tenant is scored on the first row of each of its requests (the [CLS]
+    token at the beginning of the sentence), a tagging tenant on every row; the predicted
+    label is the class with the highest score (the lowest such index on ties).
+
+    ``head_of(tenant)`` -> (W, b, per_token).  Returns (scores [N, max_classes] with -inf
+    where there is no class or no prediction, labels [N] with -1 where there is no prediction).
+    """
+    H = np.asarray(H, dtype=np.float64)
+    N = H.shape[0]
+    scores = np.full((N, max_classes), -np.inf)
+    labels = np.full(N, -1, dtype=np.int64)
+    start = 0
+    for r in range(len(tenant_ids)):
+        S = int(seq_lens[r])
+        W, b, per_token = head_of(int(tenant_ids[r]))
+        rows = range(start, start + S) if per_token else range(start, start + 1)
+        for i in rows:
+            sc = linear(H[i], np.asarray(W, dtype=np.float64), np.asarray(b, dtype=np.float64))
+            scores[i, :len(sc)] = sc
+            labels[i] = int(np.argmax(sc))      # first index of the maximum
+        start += S
+    return scores, labels

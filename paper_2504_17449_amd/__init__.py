@@ -21,7 +21,7 @@ HMI_OK, HMI_ERR_ARG, HMI_ERR_OOM, HMI_ERR_TENANT, HMI_ERR_SHAPE, HMI_ERR_CAPACIT
 HMI_F32, HMI_BF16 = 0, 1
 HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER = 0, 1, 2, 3, 4
 
-EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_layer_forward", "hmi_stack_forward",
+EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward", "hmi_layer_forward", "hmi_stack_forward",
            "hmi_get_route",
            "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
            "hmi_pool_destroy"]
@@ -32,7 +32,7 @@ class hmi_pool_config_t(C.Structure):
                 ("d_ff", C.c_int32), ("n_heads", C.c_int32), ("n_layers", C.c_int32),
                 ("max_tenants", C.c_int32), ("hbm_slots", C.c_int32), ("host_tier", C.c_int32),
                 ("max_requests", C.c_int32), ("max_tokens", C.c_int32), ("ln_eps", C.c_float),
-                ("device", C.c_int32), ("compute_stream", C.c_void_p), ("adapter_rank", C.c_int32)]
+                ("device", C.c_int32), ("compute_stream", C.c_void_p), ("adapter_rank", C.c_int32), ("max_classes", C.c_int32)]
 
 
 class HmiError(RuntimeError):
@@ -54,6 +54,10 @@ def _load() -> C.CDLL:
     lib.hmi_pool_load_tenant.restype = i32
     lib.hmi_pool_load_shared.argtypes = [vp, i32, C.POINTER(vp), i32]
     lib.hmi_pool_load_shared.restype = i32
+    lib.hmi_pool_load_head.argtypes = [vp, i32, vp, vp, i32, i32]
+    lib.hmi_pool_load_head.restype = i32
+    lib.hmi_head_forward.argtypes = [vp, vp, vp, vp]
+    lib.hmi_head_forward.restype = i32
     lib.hmi_layer_forward.argtypes = [vp, i32, vp, vp, pi32, pi32, i32]
     lib.hmi_layer_forward.restype = i32
     lib.hmi_stack_forward.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
@@ -97,12 +101,13 @@ def hmi_last_error(pool: Optional[int]) -> str:
 def hmi_pool_create(*, block: int, dtype: int, d_model: int, d_ff: int, n_heads: int = 0,
                     n_layers: int = 1, max_tenants: int, hbm_slots: Optional[int] = None,
                     host_tier: bool = False, max_requests: int, max_tokens: int,
-                    ln_eps: float = 1e-12, device: int = 0, compute_stream: int = 0, adapter_rank: int = 0):
+                    ln_eps: float = 1e-12, device: int = 0, compute_stream: int = 0, adapter_rank: int = 0,
+                    max_classes: int = 0):
     """-> (status, pool handle or None).  compute_stream: raw hipStream_t (torch's
     ``torch.cuda.current_stream().cuda_stream``), 0 = default stream."""
     cfg = hmi_pool_config_t(block, dtype, d_model, d_ff, n_heads, n_layers, max_tenants,
                             max_tenants if hbm_slots is None else hbm_slots, int(host_tier),
-                            max_requests, max_tokens, ln_eps, device, compute_stream or None, adapter_rank)
+                            max_requests, max_tokens, ln_eps, device, compute_stream or None, adapter_rank, max_classes)
     out = C.c_void_p()
     rc = lib.hmi_pool_create(C.byref(cfg), C.byref(out))
     return rc, (out.value if rc == HMI_OK else None)
@@ -121,6 +126,17 @@ def hmi_pool_load_shared(pool: int, layer: int, tensors: Sequence[np.ndarray]) -
     keep = [np.ascontiguousarray(t) for t in tensors]
     arr = (C.c_void_p * len(keep))(*[t.ctypes.data for t in keep])
     return lib.hmi_pool_load_shared(pool, layer, arr, len(keep))
+
+
+def hmi_pool_load_head(pool: int, tenant_id: int, w: np.ndarray, b: np.ndarray, per_token: bool) -> int:
+    """w [n_classes, d], b [n_classes]: host arrays in the pool's storage dtype."""
+    w, b = np.ascontiguousarray(w), np.ascontiguousarray(b)
+    return lib.hmi_pool_load_head(pool, tenant_id, w.ctypes.data, b.ctypes.data, w.shape[0], int(per_token))
+
+
+def hmi_head_forward(pool: int, h_ptr: int, scores_ptr: int, labels_ptr: int) -> int:
+    """Device addresses; scores_ptr may be 0."""
+    return lib.hmi_head_forward(pool, h_ptr, scores_ptr or None, labels_ptr)
 
 
 def hmi_layer_forward(pool: int, layer: int, x_ptr: int, y_ptr: int, tenant_ids, seq_lens) -> int:
@@ -207,6 +223,13 @@ class Pool:
 
     def load_shared(self, layer: int, tensors) -> None:
         self._check(hmi_pool_load_shared(self.h, layer, tensors))
+
+    def load_head(self, tenant_id: int, w, b, per_token: bool) -> None:
+        self._check(hmi_pool_load_head(self.h, tenant_id, w, b, per_token))
+
+    def head_forward(self, h, scores, labels) -> None:
+        """h [N, d] pool dtype, scores float32 [N, max_classes] or None, labels int32 [N]: torch tensors on the device."""
+        self._check(hmi_head_forward(self.h, h.data_ptr(), 0 if scores is None else scores.data_ptr(), labels.data_ptr()))
 
     def forward(self, layer: int, x, y, tenant_ids, seq_lens) -> None:
         """x, y: torch tensors on the pool's device ([N, d], pool dtype, contiguous)."""

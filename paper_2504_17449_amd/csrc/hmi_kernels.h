@@ -15,6 +15,7 @@ struct Route {
   const int32_t* tenant_ids;  // [R] in: request -> tenant
   const int32_t* seq_lens;    // [R] in
   const int32_t* req_slot;    // [R] in: request -> HBM slot of its tenant (resolved on host)
+  int32_t* req_tenant;        // [R]   request -> tenant (device copy of tenant_ids)
   int32_t* perm;              // [R]   sorted position -> request
   int32_t* tok_off;           // [R+1] request -> first row (original packed order)
   int32_t* seg_tenant;        // [G]
@@ -103,6 +104,16 @@ struct LnArgs {
   int d; float eps; int n_rows; int bf16;
 };
 void launch_layernorm(const LnArgs& a, const Route& rt, hipStream_t s);
+
+// Per-tenant output heads: one workgroup per request; scores[row, c] = b_t[c] + W_t[c] . h[row] in fp32,
+// labels[row] = first argmax.  heads: per tenant max_classes rows of d weights, then max_classes
+// biases (storage dtype); meta: per tenant {n_classes, per_token}.
+struct HeadArgs {
+  const void* h; float* scores; int32_t* labels;
+  const char* heads; size_t head_stride; const int32_t* meta;
+  int d, max_classes, bf16;
+};
+void launch_heads(const HeadArgs& a, const Route& rt, int R, hipStream_t s);
 
 // Per-request multi-head attention on packed qkv [N, 3d] (q | k | v) -> ctx [N, d].
 struct AttnArgs {

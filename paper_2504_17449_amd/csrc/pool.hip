@@ -111,6 +111,13 @@ struct hmi_pool {
   std::vector<uint8_t> shared_loaded;
   Route rt_dense{};            // route for GEMMs / LayerNorms that read them
 
+  // per-tenant output heads (max_classes > 0): all resident, [max_classes][d] weights + [max_classes] biases each
+  char* d_heads = nullptr;
+  size_t head_stride = 0;
+  int32_t* d_head_meta = nullptr;      // [tenant] {n_classes, per_token}
+  std::vector<uint8_t> head_loaded;
+  std::vector<int32_t> last_distinct;  // tenants of the last routed batch
+
   // workspaces
   char *w_qkv = nullptr, *w_ctx = nullptr, *w_hmid = nullptr, *w_act = nullptr;
   float *w_z = nullptr, *w_x1 = nullptr, *w_y32 = nullptr;
@@ -188,6 +195,8 @@ void free_all(hmi_pool* p) {
   if (p->copy) (void)hipStreamSynchronize(p->copy);
   (void)hipFree(p->d_pool);
   (void)hipFree(p->d_shared);
+  (void)hipFree(p->d_heads);
+  (void)hipFree(p->d_head_meta);
   (void)hipFree(p->d_idx);
   (void)hipFree(p->w_qkv); (void)hipFree(p->w_ctx); (void)hipFree(p->w_hmid);
   (void)hipFree(p->w_act); (void)hipFree(p->w_z); (void)hipFree(p->w_x1);
@@ -319,6 +328,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   if (!c.host_tier && c.hbm_slots != c.max_tenants)
     return fail(nullptr, HMI_ERR_ARG, "without host_tier every tenant needs a slot: hbm_slots must equal max_tenants");
   if (!(c.ln_eps >= 0.0f)) return fail(nullptr, HMI_ERR_ARG, "ln_eps must be >= 0");
+  if (c.max_classes < 0 || c.max_classes > 64) return fail(nullptr, HMI_ERR_ARG, "max_classes must be in [0, 64]");
 
   hmi_pool* p = new (std::nothrow) hmi_pool();
   if (!p) return fail(nullptr, HMI_ERR_OOM, "host allocation failed");
@@ -369,6 +379,13 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   }
   CREATE_TRY(hipMalloc(&p->d_pool, p->slot_stride * (size_t)c.hbm_slots));
   if (p->shared_image_bytes) CREATE_TRY(hipMalloc(&p->d_shared, p->shared_image_bytes * (size_t)c.n_layers));
+  if (c.max_classes > 0) {
+    p->head_stride = align_up((size_t)c.max_classes * (c.d_model + 1) * p->esize, kAlign);
+    CREATE_TRY(hipMalloc(&p->d_heads, p->head_stride * (size_t)c.max_tenants));
+    CREATE_TRY(hipMalloc(&p->d_head_meta, sizeof(int32_t) * 2 * (size_t)c.max_tenants));
+    CREATE_TRY(hipMemset(p->d_head_meta, 0, sizeof(int32_t) * 2 * (size_t)c.max_tenants));
+    p->head_loaded.assign(c.max_tenants, 0);
+  }
 
   p->slot_of_tenant.assign(c.max_tenants, -1);
   p->tenant_of_slot.assign(c.hbm_slots, -1);
@@ -399,6 +416,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   const size_t max_tiles0 = MT / p->tile_m[0] + Rm + 1;
   const size_t max_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + Rm + 1 : 0;
   size_t n_i32 = 3 * (size_t)Rm            // ids, lens, req_slot
+                 + Rm                      // req_tenant
                  + Rm + (Rm + 1)           // perm, tok_off
                  + 2 * (size_t)Rm          // seg_tenant, seg_slot
                  + 2 * ((size_t)Rm + 1)    // seg_req_off, seg_tok_off
@@ -415,6 +433,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   auto take = [&](size_t n) { int32_t* r = q; q += n; return r; };
   Route& rt = p->rt;
   rt.tenant_ids = take(Rm); rt.seq_lens = take(Rm); rt.req_slot = take(Rm);
+  rt.req_tenant = take(Rm);
   rt.perm = take(Rm); rt.tok_off = take(Rm + 1);
   rt.seg_tenant = take(Rm); rt.seg_slot = take(Rm);
   rt.seg_req_off = take(Rm + 1); rt.seg_tok_off = take(Rm + 1);
@@ -564,6 +583,43 @@ int32_t hmi_pool_load_shared(hmi_pool_t* p, int32_t layer, const void* const* te
   return HMI_OK;
 }
 
+int32_t hmi_pool_load_head(hmi_pool_t* p, int32_t tenant, const void* w, const void* b, int32_t n_classes,
+                           int32_t per_token) {
+  if (!p) return HMI_ERR_ARG;
+  const hmi_pool_config_t& c = p->cfg;
+  if (c.max_classes <= 0) return fail(p, HMI_ERR_ARG, "the pool was created without output heads (max_classes = 0)");
+  if (!w || !b) return fail(p, HMI_ERR_ARG, "null head tensor");
+  if (tenant < 0 || tenant >= c.max_tenants) return fail(p, HMI_ERR_TENANT, "tenant %d outside [0,%d)", tenant, c.max_tenants);
+  if (n_classes < 1 || n_classes > c.max_classes) return fail(p, HMI_ERR_SHAPE, "n_classes %d outside [1,%d]", n_classes, c.max_classes);
+  HIP_TRY(p, hipSetDevice(c.device));
+  if (p->head_loaded[tenant]) HIP_TRY(p, hipStreamSynchronize(p->compute));   // may still be read
+  char* dst = p->d_heads + (size_t)tenant * p->head_stride;
+  HIP_TRY(p, hipMemcpy(dst, w, (size_t)n_classes * c.d_model * p->esize, hipMemcpyHostToDevice));
+  HIP_TRY(p, hipMemcpy(dst + (size_t)c.max_classes * c.d_model * p->esize, b, (size_t)n_classes * p->esize, hipMemcpyHostToDevice));
+  const int32_t meta[2] = {n_classes, per_token ? 1 : 0};
+  HIP_TRY(p, hipMemcpy(p->d_head_meta + 2 * (size_t)tenant, meta, sizeof(meta), hipMemcpyHostToDevice));
+  p->head_loaded[tenant] = 1;
+  return HMI_OK;
+}
+
+int32_t hmi_head_forward(hmi_pool_t* p, const void* h, float* scores, int32_t* labels) {
+  if (!p) return HMI_ERR_ARG;
+  const hmi_pool_config_t& c = p->cfg;
+  if (c.max_classes <= 0) return fail(p, HMI_ERR_ARG, "the pool was created without output heads (max_classes = 0)");
+  if (!h || !labels) return fail(p, HMI_ERR_ARG, "null pointer");
+  if (p->last_R <= 0) return fail(p, HMI_ERR_ARG, "no forward call has routed a batch yet");
+  for (int t : p->last_distinct)
+    if (!p->head_loaded[t]) return fail(p, HMI_ERR_TENANT, "tenant %d has no output head", t);
+  HIP_TRY(p, hipSetDevice(c.device));
+  HeadArgs a{};
+  a.h = h; a.scores = scores; a.labels = labels;
+  a.heads = p->d_heads; a.head_stride = p->head_stride; a.meta = p->d_head_meta;
+  a.d = c.d_model; a.max_classes = c.max_classes; a.bf16 = p->bf16;
+  launch_heads(a, p->rt, p->last_R, p->compute);
+  HIP_TRY(p, hipGetLastError());
+  return HMI_OK;
+}
+
 int32_t hmi_pool_prefetch(hmi_pool_t* p, int32_t layer, const int32_t* ids, int32_t n) {
   if (!p) return HMI_ERR_ARG;
   if (n < 0 || (n > 0 && !ids)) return fail(p, HMI_ERR_ARG, "bad tenant list");
@@ -696,6 +752,7 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
   { ProfSpan ps(p, HMI_KERNEL_ROUTER); launch_router(rt, R, s); }
   HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
   p->last_R = R;
+  p->last_distinct = p->distinct;
 
   const int d = c.d_model, f = c.d_ff;
   const bool f32 = !p->bf16;  // fp32 pools: "storage" and fp32 coincide

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
       slot_r[c] = i < R ? rt.req_slot[i] : 0;
       int tot;
       int ex = block_exscan(len, wave_tot, tot) + carry;
-      if (i < R) { tok_s[i] = ex; rt.tok_off[i] = ex; key[0][i] = tenant; val[0][i] = i; }
+      if (i < R) { tok_s[i] = ex; rt.tok_off[i] = ex; rt.req_tenant[i] = tenant; key[0][i] = tenant; val[0][i] = i; }
       carry += tot;
     }
   }

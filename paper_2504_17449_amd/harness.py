@@ -22,16 +22,21 @@ def create_pool(wl: synth.Workload, *, max_requests: Optional[int] = None,
                 d_model=wl.d_model, d_ff=wl.d_ff, n_heads=wl.n_heads, n_layers=wl.n_layers,
                 max_tenants=wl.n_tenants, hbm_slots=hbm_slots or wl.hbm_slots,
                 host_tier=wl.host_tier, max_requests=R, max_tokens=max_tokens or R * wl.seq_max,
-                ln_eps=wl.ln_eps, device=device, compute_stream=stream, adapter_rank=wl.adapter_rank)
+                ln_eps=wl.ln_eps, device=device, compute_stream=stream, adapter_rank=wl.adapter_rank, max_classes=wl.max_classes)
 
 
 def load_tenants(pool: Pool, wl: synth.Workload, tenants: Optional[Iterable[int]] = None,
                  workers: int = 8) -> None:
     """Generate and register every (tenant, layer) of ``tenants`` (default: all)."""
+    tenants = list(range(wl.n_tenants)) if tenants is None else list(tenants)
     if synth.shared_specs(wl):
         for l in range(wl.n_layers):
             pool.load_shared(l, synth.shared_storage(wl, l))
-    todo = [(t, l) for t in (range(wl.n_tenants) if tenants is None else tenants)
+    if wl.max_classes:
+        for t in tenants:
+            w, b = synth.head_tensors(wl, t, raw=True)
+            pool.load_head(t, w, b, synth.head_spec(wl, t)[1])
+    todo = [(t, l) for t in tenants
             for l in range(wl.n_layers)]
 
     def gen(tl):

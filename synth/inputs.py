@@ -26,7 +26,8 @@ BLOCK_ENC_ADAPTER = 4  # shared post-LN encoder layer + per-tenant adapter after
 
 SHARED = 0x7FFFFFFF    # "tenant" key of the parameters every tenant shares
 
-_TAG_WEIGHT, _TAG_X, _TAG_IDS, _TAG_LENS = 1, 2, 3, 4
+_TAG_WEIGHT, _TAG_X, _TAG_IDS, _TAG_LENS, _TAG_HEAD = 1, 2, 3, 4, 5
+_HEAD_LAYER = 1 << 20  # "layer" key of a tenant's output head
 
 
 @dataclass(frozen=True)
@@ -49,6 +50,7 @@ class Workload:
     host_tier: bool       # pinned-host pool + HBM cache + swap-in
     seed: int = 0
     adapter_rank: int = 0  # BLOCK_ENC_ADAPTER: bottleneck width of the per-tenant adapter
+    max_classes: int = 0   # > 0: every tenant also owns an output head with at most this many classes
 
     def scaled(self, **kw) -> "Workload":
         """Same recipe at another size (tests use reduced tenant / request counts)."""
@@ -71,7 +73,7 @@ WORKLOADS = {
     # The paper's own serving layer: the 6 higher BERT-base layers shared by all tenants, each
     # with the tenant's adapter after its attention layer (Sec. 3.2.2, Sec. 3.3 footnote).
     "hbert_shared_adapter": Workload("hbert_shared_adapter", BLOCK_ENC_ADAPTER, "bf16", 768, 3072, 12, 6, 1000,
-                                     512, 128, 128, "zipf", 1.1, 1e-12, 1000, False, adapter_rank=64),
+                                     512, 128, 128, "zipf", 1.1, 1e-12, 1000, False, adapter_rank=64, max_classes=32),
     # Paper-exact bottleneck adapter (Sec. 3.2.2); rank 64 is this build's reading.
     "hbert_adapter": Workload("hbert_adapter", BLOCK_ADAPTER, "bf16", 768, 64, 0, 1, 1000, 512,
                               128, 128, "zipf", 1.1, 0.0, 1000, False),
@@ -227,6 +229,26 @@ def shared_tensors(wl: Workload, layer: int = 0) -> List[np.ndarray]:
 
 def shared_storage(wl: Workload, layer: int = 0) -> List[np.ndarray]:
     return [_tensor(wl, SHARED, layer, 100 + i, shape, kind, True) for i, (_, shape, kind) in enumerate(shared_specs(wl))]
+
+
+def head_spec(wl: Workload, tenant: int) -> Tuple[int, bool]:
+    """(number of classes, per_token) of a tenant's output head.  Three tenants in ten tag every
+    token, the others classify on the first row (the task mix of the paper's Table of datasets);
+    class counts are uniform on [2, max_classes] (classification) or odd counts from 3 up
+    (BIO tag sets) within the same bound."""
+    g = _gen(wl.seed, _TAG_HEAD, tenant)
+    per_token = bool(g.random() < 0.3)
+    c = int(g.integers(2, wl.max_classes + 1))
+    if per_token:
+        c = min(max(3, c | 1), wl.max_classes)
+    return c, per_token
+
+
+def head_tensors(wl: Workload, tenant: int, raw: bool = False) -> List[np.ndarray]:
+    """W [C, d] and b [C] of a tenant's head ~ N(0, 0.02), storage-exact fp32 (or storage bytes)."""
+    c, _ = head_spec(wl, tenant)
+    return [_tensor(wl, tenant, _HEAD_LAYER, 0, (c, wl.d_model), "w", raw),
+            _tensor(wl, tenant, _HEAD_LAYER, 1, (c,), "b", raw)]
 
 
 def hidden_states(wl: Workload, request: int, seq_len: int, batch: int = 0) -> np.ndarray:

@@ -32,7 +32,7 @@ def pick_sample(ids, lens, n_multi=8, n_single=16):
     return sorted(sample)
 
 
-def run_full(wl, sample_kw=None, tenants=None):
+def run_full(wl, sample_kw=None, tenants=None, heads=False):
     from paper_2504_17449_amd import harness
     t0 = time.time()
     ids, lens, x = harness.batch_to_device(wl)
@@ -48,6 +48,10 @@ def run_full(wl, sample_kw=None, tenants=None):
         torch.cuda.synchronize()
         check_route(pool, ids, lens)
         y_gpu = harness.device_to_f64(y)
+        if heads:   # the tenants' output heads on the (seeded) input hidden states of the same batch
+            from tests.test_gpu_parity import check_heads
+            X64 = np.concatenate([synth.hidden_states(wl, r, int(lens[r])) for r in range(len(ids))]).astype(np.float64)
+            check_heads(pool, wl, ids, lens, x, X64)
     finally:
         pool.close()
     sample = pick_sample(ids, lens, **(sample_kw or {}))
@@ -74,7 +78,7 @@ def test_adapter_block_1000_tenants_full_size():
 
 def test_shared_layers_with_adapters_1000_tenants_full_size():
     """The six shared higher layers with per-tenant adapters, as bench.py --workload hbert_shared_adapter runs them."""
-    run_full(synth.WORKLOADS["hbert_shared_adapter"], sample_kw=dict(n_multi=4, n_single=6))
+    run_full(synth.WORKLOADS["hbert_shared_adapter"], sample_kw=dict(n_multi=4, n_single=6), heads=True)
 
 
 # ------------------------------------------------------------------ host tier

@@ -240,6 +240,55 @@ def test_shared_layer_with_loud_adapters(hmi):
     assert ok, (max_abs, rel)
 
 
+def check_heads(pool, wl, ids, lens, x, X64):
+    """Output heads on seeded hidden states after a forward call has routed the batch: scores to the
+    fp32 bar, labels exact wherever the oracle's two best scores are further apart than that bar."""
+    N = int(lens.sum())
+    scores = torch.full((N, wl.max_classes), float("nan"), dtype=torch.float32, device=x.device)
+    labels = torch.full((N,), -7, dtype=torch.int32, device=x.device)
+    pool.head_forward(x, scores, labels)
+    torch.cuda.synchronize()
+    heads = {t: tuple(a.astype(np.float64) for a in synth.head_tensors(wl, t)) + (synth.head_spec(wl, t)[1],)
+             for t in set(ids.tolist())}
+    sc_ref, lab_ref = O.head_forward(X64, ids, lens, lambda t: heads[t], wl.max_classes)
+    sc, lab = scores.cpu().numpy().astype(np.float64), labels.cpu().numpy()
+    assert np.array_equal(np.isneginf(sc), np.isneginf(sc_ref))
+    fin = np.isfinite(sc_ref)
+    assert np.isfinite(sc[fin]).all()
+    err = np.abs(sc[fin] - sc_ref[fin]).max()
+    top2 = np.sort(np.where(fin, sc_ref, -np.inf), axis=1)[:, -2:]
+    clear = (lab_ref < 0) | (top2[:, 1] - top2[:, 0] > 1e-4)
+    print(f"  heads: {int((lab_ref >= 0).sum())} predictions, max score error {err:.2e}, "
+          f"{int((~clear).sum())} near-ties, tagging tenants {sum(h[2] for h in heads.values())}/{len(heads)}", flush=True)
+    assert err <= 1e-4
+    np.testing.assert_array_equal(lab[clear], lab_ref[clear])
+    assert ((lab == lab_ref) | ~clear).all() and (lab[~clear] >= 0).all()
+    # labels only
+    labels2 = torch.full_like(labels, -7)
+    pool.head_forward(x, None, labels2)
+    torch.cuda.synchronize()
+    assert torch.equal(labels, labels2)
+
+
+@pytest.mark.parametrize("dtype,d_model", [("bf16", 128), ("bf16", 768), ("f32", 64)])
+def test_output_heads_ragged(hmi, dtype, d_model):
+    """Sec. 3.3.2: per-tenant linear heads with their own class counts, classification tenants on
+    the first row of a request, tagging tenants on every row, label = highest score."""
+    from paper_2504_17449_amd import harness
+    wl = small(synth.BLOCK_ADAPTER, dtype, d_model=d_model, d_ff=64 if dtype == "bf16" else 16, n_tenants=40,
+               hbm_slots=40, n_requests=60, seq_max=70, max_classes=9)
+    ids, lens, x = harness.batch_to_device(wl)
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl, sorted(set(ids.tolist())))
+        y = torch.empty_like(x)
+        pool.forward(0, x, y, ids, lens)
+        X64 = np.concatenate([synth.hidden_states(wl, r, int(lens[r])) for r in range(len(ids))]).astype(np.float64)
+        check_heads(pool, wl, ids, lens, x, X64)
+    finally:
+        pool.close()
+
+
 def test_bert_ffn_full_size_sampled(hmi):
     wl = synth.WORKLOADS["bert_ffn"]
     ids, _ = synth.batch_ids_lens(wl)

@@ -490,6 +490,46 @@ def test_route_against_rank_count(R, T):
         assert rt["seg_tok_off"][g + 1] - rt["seg_tok_off"][g] == sum(lens[q] for q in members)
 
 
+# ------------------------------------------------------------------ output heads
+
+def test_head_forward_hand_worked():
+    """Sec. 3.3.2: classification on the first row of a request, tagging on every row, label =
+    class of the highest score.  Tenant 0 classifies with W = [[1,0],[0,1],[1,1]], b = [0,0,-10];
+    tenant 1 tags with W = [[2,-1],[-1,2]], b = [0.5,0].  Rows: request 0 (tenant 1): [1,0],[0,1];
+    request 1 (tenant 0): [3,4],[9,9]."""
+    H = np.array([[1.0, 0], [0, 1], [3, 4], [9, 9]])
+    heads = {0: (np.array([[1.0, 0], [0, 1], [1, 1]]), np.array([0.0, 0, -10]), False),
+             1: (np.array([[2.0, -1], [-1, 2]]), np.array([0.5, 0.0]), True)}
+    sc, lab = O.head_forward(H, [1, 0], [2, 2], lambda t: heads[t], 4)
+    inf = -np.inf
+    np.testing.assert_array_equal(sc, [[2.5, -1, inf, inf], [-0.5, 2, inf, inf], [3, 4, -3, inf], [inf] * 4])
+    assert lab.tolist() == [0, 1, 1, -1]
+
+
+def test_head_forward_ties_and_brute_force():
+    rng = np.random.default_rng(5)
+    d, T = 6, 4
+    heads = {t: (rng.standard_normal((2 + t, d)), rng.standard_normal(2 + t), bool(t % 2)) for t in range(T)}
+    ids, lens = [3, 0, 2, 1, 0], [3, 2, 1, 4, 1]
+    H = rng.standard_normal((sum(lens), d))
+    sc, lab = O.head_forward(H, ids, lens, lambda t: heads[t], 8)
+    row = 0
+    for t, S in zip(ids, lens):
+        W, b, per_token = heads[t]
+        for i in range(S):
+            if per_token or i == 0:
+                want = [sum(W[c][k] * H[row][k] for k in range(d)) + b[c] for c in range(len(b))]
+                np.testing.assert_allclose(sc[row, :len(b)], want, rtol=1e-13, atol=1e-13)
+                assert np.all(np.isneginf(sc[row, len(b):]))
+                assert lab[row] == max(range(len(b)), key=lambda c: (want[c], -c))
+            else:
+                assert lab[row] == -1 and np.all(np.isneginf(sc[row]))
+            row += 1
+    # equal scores: the lowest class index wins
+    tie = {0: (np.zeros((3, d)), np.array([1.0, 2.0, 2.0]), False)}
+    assert O.head_forward(H[:1], [0], [1], lambda t: tie[t], 3)[1].tolist() == [1]
+
+
 # ------------------------------------------------------------------ the pins do bite
 
 MUTANTS = {
