@@ -154,6 +154,23 @@ def main() -> int:
                          "bytes_per_launch": algo_bytes})
         del roofline["flop_per_launch"]
 
+    # ---- per-tenant output heads on the step's result (not part of the step: reported beside it)
+    heads = None
+    if wl.max_classes:
+        scores = torch.empty((N, wl.max_classes), dtype=torch.float32, device="cuda")
+        labels = torch.empty((N,), dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            pool.head_forward(y, scores, labels)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            pool.head_forward(y, scores, labels)
+        e1.record()
+        torch.cuda.synchronize()
+        n_pred = int((labels >= 0).sum().item())
+        heads = {"ms_per_call": round(e0.elapsed_time(e1) / args.steps, 5), "predictions": n_pred,
+                 "max_classes": wl.max_classes}
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same batch
     cpu = None
     if args.cpu_sample > 0:
@@ -201,6 +218,7 @@ def main() -> int:
                               max(1, stats1["hits"] - stats0["hits"] + stats1["misses"] - stats0["misses"]), 4),
             "h2d_GB_per_s": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / elapsed / 1e9, 2),
             "h2d_MB_per_step": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / args.steps / 1e6, 1)},
+        "heads": heads,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -105,15 +105,18 @@ struct LnArgs {
 };
 void launch_layernorm(const LnArgs& a, const Route& rt, hipStream_t s);
 
-// Per-tenant output heads: one workgroup per request; scores[row, c] = b_t[c] + W_t[c] . h[row] in fp32,
-// labels[row] = first argmax.  heads: per tenant max_classes rows of d weights, then max_classes
-// biases (storage dtype); meta: per tenant {n_classes, per_token}.
+// Per-tenant output heads.  A head image holds kHeadCols class rows of d weights (rows at or
+// beyond the tenant's class count are zero) and then kHeadCols biases, in the storage dtype, so
+// that raw[row, c] = b_t[c] + W_t[c] . h[row] is a grouped GEMM with n_out = kHeadCols and fp32
+// output.  launch_head_select masks raw by the tenant's {n_classes, per_token} (meta), writes the
+// scores [N, max_classes] (optional) and labels[row] = first arg-max (-1: no prediction).
+constexpr int kHeadCols = 64;
 struct HeadArgs {
-  const void* h; float* scores; int32_t* labels;
-  const char* heads; size_t head_stride; const int32_t* meta;
-  int d, max_classes, bf16;
+  const float* raw; float* scores; int32_t* labels;
+  const int32_t* meta;
+  int max_classes;
 };
-void launch_heads(const HeadArgs& a, const Route& rt, int R, hipStream_t s);
+void launch_head_select(const HeadArgs& a, const Route& rt, int R, hipStream_t s);
 
 // Per-request multi-head attention on packed qkv [N, 3d] (q | k | v) -> ctx [N, d].
 struct AttnArgs {

@@ -111,12 +111,14 @@ struct hmi_pool {
   std::vector<uint8_t> shared_loaded;
   Route rt_dense{};            // route for GEMMs / LayerNorms that read them
 
-  // per-tenant output heads (max_classes > 0): all resident, [max_classes][d] weights + [max_classes] biases each
+  // per-tenant output heads (max_classes > 0): all resident, [kHeadCols][d] weights + [kHeadCols] biases each
   char* d_heads = nullptr;
   size_t head_stride = 0;
   int32_t* d_head_meta = nullptr;      // [tenant] {n_classes, per_token}
   std::vector<uint8_t> head_loaded;
   std::vector<int32_t> last_distinct;  // tenants of the last routed batch
+  int last_n_mtiles[2] = {0, 0};       // its m-tile counts
+  float* w_scores = nullptr;           // [max_tokens, kHeadCols] raw scores
 
   // workspaces
   char *w_qkv = nullptr, *w_ctx = nullptr, *w_hmid = nullptr, *w_act = nullptr;
@@ -197,6 +199,7 @@ void free_all(hmi_pool* p) {
   (void)hipFree(p->d_shared);
   (void)hipFree(p->d_heads);
   (void)hipFree(p->d_head_meta);
+  (void)hipFree(p->w_scores);
   (void)hipFree(p->d_idx);
   (void)hipFree(p->w_qkv); (void)hipFree(p->w_ctx); (void)hipFree(p->w_hmid);
   (void)hipFree(p->w_act); (void)hipFree(p->w_z); (void)hipFree(p->w_x1);
@@ -380,8 +383,10 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   CREATE_TRY(hipMalloc(&p->d_pool, p->slot_stride * (size_t)c.hbm_slots));
   if (p->shared_image_bytes) CREATE_TRY(hipMalloc(&p->d_shared, p->shared_image_bytes * (size_t)c.n_layers));
   if (c.max_classes > 0) {
-    p->head_stride = align_up((size_t)c.max_classes * (c.d_model + 1) * p->esize, kAlign);
+    p->head_stride = align_up((size_t)kHeadCols * (c.d_model + 1) * p->esize, kAlign);
     CREATE_TRY(hipMalloc(&p->d_heads, p->head_stride * (size_t)c.max_tenants));
+    CREATE_TRY(hipMemset(p->d_heads, 0, p->head_stride * (size_t)c.max_tenants));
+    CREATE_TRY(hipMalloc(&p->w_scores, (size_t)c.max_tokens * kHeadCols * sizeof(float)));
     CREATE_TRY(hipMalloc(&p->d_head_meta, sizeof(int32_t) * 2 * (size_t)c.max_tenants));
     CREATE_TRY(hipMemset(p->d_head_meta, 0, sizeof(int32_t) * 2 * (size_t)c.max_tenants));
     p->head_loaded.assign(c.max_tenants, 0);
@@ -594,8 +599,9 @@ int32_t hmi_pool_load_head(hmi_pool_t* p, int32_t tenant, const void* w, const v
   HIP_TRY(p, hipSetDevice(c.device));
   if (p->head_loaded[tenant]) HIP_TRY(p, hipStreamSynchronize(p->compute));   // may still be read
   char* dst = p->d_heads + (size_t)tenant * p->head_stride;
+  if (p->head_loaded[tenant]) HIP_TRY(p, hipMemset(dst, 0, p->head_stride));   // rows the new head does not have
   HIP_TRY(p, hipMemcpy(dst, w, (size_t)n_classes * c.d_model * p->esize, hipMemcpyHostToDevice));
-  HIP_TRY(p, hipMemcpy(dst + (size_t)c.max_classes * c.d_model * p->esize, b, (size_t)n_classes * p->esize, hipMemcpyHostToDevice));
+  HIP_TRY(p, hipMemcpy(dst + (size_t)kHeadCols * c.d_model * p->esize, b, (size_t)n_classes * p->esize, hipMemcpyHostToDevice));
   const int32_t meta[2] = {n_classes, per_token ? 1 : 0};
   HIP_TRY(p, hipMemcpy(p->d_head_meta + 2 * (size_t)tenant, meta, sizeof(meta), hipMemcpyHostToDevice));
   p->head_loaded[tenant] = 1;
@@ -611,11 +617,20 @@ int32_t hmi_head_forward(hmi_pool_t* p, const void* h, float* scores, int32_t* l
   for (int t : p->last_distinct)
     if (!p->head_loaded[t]) return fail(p, HMI_ERR_TENANT, "tenant %d has no output head", t);
   HIP_TRY(p, hipSetDevice(c.device));
+  // raw scores: grouped GEMM over the tenant route of that batch; heads are indexed by tenant, not by slot
+  Route rh = p->rt;
+  rh.seg_slot = p->rt.seg_tenant;
+  GemmArgs g{};
+  g.A = h; g.lda = c.d_model; g.C = p->w_scores; g.ldc = kHeadCols; g.out_f32 = 1;
+  g.pool = p->d_heads; g.slot_stride = p->head_stride;
+  g.w_off = 0; g.b_off = (size_t)kHeadCols * c.d_model * p->esize;
+  g.n_out = kHeadCols; g.k = c.d_model; g.epi = EPI_BIAS;
+  g.n_mtiles_list[0] = p->last_n_mtiles[0]; g.n_mtiles_list[1] = p->last_n_mtiles[1];
+  g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
+  if (p->bf16) launch_gemm_bf16(g, rh, p->compute); else launch_gemm_f32(g, rh, p->compute);
   HeadArgs a{};
-  a.h = h; a.scores = scores; a.labels = labels;
-  a.heads = p->d_heads; a.head_stride = p->head_stride; a.meta = p->d_head_meta;
-  a.d = c.d_model; a.max_classes = c.max_classes; a.bf16 = p->bf16;
-  launch_heads(a, p->rt, p->last_R, p->compute);
+  a.raw = p->w_scores; a.scores = scores; a.labels = labels; a.meta = p->d_head_meta; a.max_classes = c.max_classes;
+  launch_head_select(a, p->rt, p->last_R, p->compute);
   HIP_TRY(p, hipGetLastError());
   return HMI_OK;
 }
@@ -753,6 +768,7 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
   HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
   p->last_R = R;
   p->last_distinct = p->distinct;
+  p->last_n_mtiles[0] = n_mtiles[0]; p->last_n_mtiles[1] = n_mtiles[1];
 
   const int d = c.d_model, f = c.d_ff;
   const bool f32 = !p->bf16;  // fp32 pools: "storage" and fp32 coincide

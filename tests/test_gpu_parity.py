@@ -257,7 +257,8 @@ def check_heads(pool, wl, ids, lens, x, X64):
     assert np.isfinite(sc[fin]).all()
     err = np.abs(sc[fin] - sc_ref[fin]).max()
     top2 = np.sort(np.where(fin, sc_ref, -np.inf), axis=1)[:, -2:]
-    clear = (lab_ref < 0) | (top2[:, 1] - top2[:, 0] > 1e-4)
+    with np.errstate(invalid="ignore"):     # rows without a prediction: -inf - -inf
+        clear = (lab_ref < 0) | (top2[:, 1] - top2[:, 0] > 1e-4)
     print(f"  heads: {int((lab_ref >= 0).sum())} predictions, max score error {err:.2e}, "
           f"{int((~clear).sum())} near-ties, tagging tenants {sum(h[2] for h in heads.values())}/{len(heads)}", flush=True)
     assert err <= 1e-4
