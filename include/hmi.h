@@ -133,6 +133,27 @@ int32_t hmi_stack_forward(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_e
                           const void* x, void* y, const int32_t* tenant_ids,
                           const int32_t* seq_lens, int32_t n_requests);
 
+/* Autoregressive decoding for bf16 DEC_PRELN pools (the paper reports its GPT-style instances in
+ * generated tokens per second, Sec. 7): a key/value cache of max_seqs lines ("sequence slots") of
+ * max_len positions for every layer of the pool, owned by the library.  Once per pool; other
+ * pools -> HMI_ERR_ARG; HMI_ERR_OOM when it does not fit. */
+int32_t hmi_kv_create(hmi_pool_t* pool, int32_t max_seqs, int32_t max_len);
+
+/* hmi_stack_forward that also records every row's key and value: request r's rows fill line
+ * seq_slots[r] (HOST int32[n_requests], distinct within a call) from position 0 and set its
+ * length to seq_lens[r] (<= max_len, else HMI_ERR_SHAPE).  Same results, errors and asynchrony. */
+int32_t hmi_prefill(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
+                    const int32_t* tenant_ids, const int32_t* seq_lens, const int32_t* seq_slots,
+                    int32_t n_requests);
+
+/* One new token per request: x, y DEVICE [n_requests, d_model].  Row r passes through the layers
+ * of tenant_ids[r]; in each layer its key and value are appended to line seq_slots[r] and it
+ * attends to all positions of that line, itself included (causal attention over the sequence so
+ * far: the result equals the last row of a full forward over the whole sequence).  The line's
+ * length grows by one (beyond max_len -> HMI_ERR_SHAPE before anything is enqueued). */
+int32_t hmi_decode_step(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
+                        const int32_t* tenant_ids, const int32_t* seq_slots, int32_t n_requests);
+
 /* Per-tenant output heads (Sec. 3.3.2): one linear layer per tenant on the final hidden states,
  * with the tenant's own number of classes.  A classification tenant (per_token = 0) is scored on
  * the first row of each of its requests (the [CLS] token at the beginning of the sentence), a

@@ -21,7 +21,8 @@ HMI_OK, HMI_ERR_ARG, HMI_ERR_OOM, HMI_ERR_TENANT, HMI_ERR_SHAPE, HMI_ERR_CAPACIT
 HMI_F32, HMI_BF16 = 0, 1
 HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER = 0, 1, 2, 3, 4
 
-EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward", "hmi_layer_forward", "hmi_stack_forward",
+EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward",
+           "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_layer_forward", "hmi_stack_forward",
            "hmi_get_route",
            "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
            "hmi_pool_destroy"]
@@ -58,6 +59,12 @@ def _load() -> C.CDLL:
     lib.hmi_pool_load_head.restype = i32
     lib.hmi_head_forward.argtypes = [vp, vp, vp, vp]
     lib.hmi_head_forward.restype = i32
+    lib.hmi_kv_create.argtypes = [vp, i32, i32]
+    lib.hmi_kv_create.restype = i32
+    lib.hmi_prefill.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, pi32, i32]
+    lib.hmi_prefill.restype = i32
+    lib.hmi_decode_step.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
+    lib.hmi_decode_step.restype = i32
     lib.hmi_layer_forward.argtypes = [vp, i32, vp, vp, pi32, pi32, i32]
     lib.hmi_layer_forward.restype = i32
     lib.hmi_stack_forward.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
@@ -137,6 +144,25 @@ def hmi_pool_load_head(pool: int, tenant_id: int, w: np.ndarray, b: np.ndarray, 
 def hmi_head_forward(pool: int, h_ptr: int, scores_ptr: int, labels_ptr: int) -> int:
     """Device addresses; scores_ptr may be 0."""
     return lib.hmi_head_forward(pool, h_ptr, scores_ptr or None, labels_ptr)
+
+
+def hmi_kv_create(pool: int, max_seqs: int, max_len: int) -> int:
+    return lib.hmi_kv_create(pool, max_seqs, max_len)
+
+
+def hmi_prefill(pool: int, layer_begin: int, layer_end: int, x_ptr: int, y_ptr: int, tenant_ids, seq_lens,
+                seq_slots) -> int:
+    ids, lens, slots = _i32(tenant_ids), _i32(seq_lens), _i32(seq_slots)
+    if not (ids.shape == lens.shape == slots.shape) or ids.ndim != 1:
+        raise ValueError("tenant_ids, seq_lens and seq_slots must be 1-D and of equal length")
+    return lib.hmi_prefill(pool, layer_begin, layer_end, x_ptr, y_ptr, _p32(ids), _p32(lens), _p32(slots), ids.shape[0])
+
+
+def hmi_decode_step(pool: int, layer_begin: int, layer_end: int, x_ptr: int, y_ptr: int, tenant_ids, seq_slots) -> int:
+    ids, slots = _i32(tenant_ids), _i32(seq_slots)
+    if ids.shape != slots.shape or ids.ndim != 1:
+        raise ValueError("tenant_ids and seq_slots must be 1-D and of equal length")
+    return lib.hmi_decode_step(pool, layer_begin, layer_end, x_ptr, y_ptr, _p32(ids), _p32(slots), ids.shape[0])
 
 
 def hmi_layer_forward(pool: int, layer: int, x_ptr: int, y_ptr: int, tenant_ids, seq_lens) -> int:
@@ -223,6 +249,15 @@ class Pool:
 
     def load_shared(self, layer: int, tensors) -> None:
         self._check(hmi_pool_load_shared(self.h, layer, tensors))
+
+    def kv_create(self, max_seqs: int, max_len: int) -> None:
+        self._check(hmi_kv_create(self.h, max_seqs, max_len))
+
+    def prefill(self, layer_begin: int, layer_end: int, x, y, tenant_ids, seq_lens, seq_slots) -> None:
+        self._check(hmi_prefill(self.h, layer_begin, layer_end, x.data_ptr(), y.data_ptr(), tenant_ids, seq_lens, seq_slots))
+
+    def decode_step(self, layer_begin: int, layer_end: int, x, y, tenant_ids, seq_slots) -> None:
+        self._check(hmi_decode_step(self.h, layer_begin, layer_end, x.data_ptr(), y.data_ptr(), tenant_ids, seq_slots))
 
     def load_head(self, tenant_id: int, w, b, per_token: bool) -> None:
         self._check(hmi_pool_load_head(self.h, tenant_id, w, b, per_token))

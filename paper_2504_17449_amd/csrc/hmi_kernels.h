@@ -33,6 +33,11 @@ struct Route {
   // scratch of the persistent GEMM: per XCD a tile-claim counter [0..7] and a count of finished
   // workgroups [8..15], then one mailbox per workgroup; all zero between launches
   int32_t* gemm_sched;
+  // Decoding with a key/value cache: per request the cache line (sequence slot) and the position
+  // its first row takes in it; copied from the *_in arrays (may be host memory) when those are set.
+  const int32_t* kv_slot_in; const int32_t* kv_pos_in;
+  int32_t* kv_slot;           // [R]
+  int32_t* kv_pos;            // [R]
   // Written by the router when not null: the segment offsets of a second route over the same
   // N rows for parameters that all tenants share.  That route takes the rows in their
   // original order and cuts them into pseudo-segments of kDenseSegRows rows (the last one
@@ -124,5 +129,15 @@ struct AttnArgs {
   int n_rows;  // N = total rows (fp32 kernel: one wavefront per row and head)
 };
 void launch_attention(const AttnArgs& a, const Route& rt, hipStream_t s);
+
+// Key/value cache of one layer: [slot][k | v][head][position][64] bf16.
+struct KvArgs {
+  const void* qkv;     // bf16 [N, 3d] of the batch (q | k | v)
+  void* ctx;           // decode: bf16 [N, d] attention output (N = R, one row per request)
+  uint16_t* cache;     // the layer's lines
+  int d, n_heads, max_len;
+};
+void launch_kv_store(const KvArgs& a, const Route& rt, int R, hipStream_t s);
+void launch_attn_decode(const KvArgs& a, const Route& rt, int R, hipStream_t s);
 
 }  // namespace hmi

@@ -120,6 +120,13 @@ struct hmi_pool {
   int last_n_mtiles[2] = {0, 0};       // its m-tile counts
   float* w_scores = nullptr;           // [max_tokens, kHeadCols] raw scores
 
+  // key/value cache for decoding (hmi_kv_create): [layer][sequence slot][k | v][head][position][64] bf16
+  uint16_t* d_kv = nullptr;
+  int kv_seqs = 0, kv_max_len = 0;
+  std::vector<int32_t> kv_len;         // positions held per sequence slot
+  std::vector<uint32_t> kv_mark;       // duplicate check per call
+  uint32_t kv_epoch = 0;
+
   // workspaces
   char *w_qkv = nullptr, *w_ctx = nullptr, *w_hmid = nullptr, *w_act = nullptr;
   float *w_z = nullptr, *w_x1 = nullptr, *w_y32 = nullptr;
@@ -200,6 +207,7 @@ void free_all(hmi_pool* p) {
   (void)hipFree(p->d_heads);
   (void)hipFree(p->d_head_meta);
   (void)hipFree(p->w_scores);
+  (void)hipFree(p->d_kv);
   (void)hipFree(p->d_idx);
   (void)hipFree(p->w_qkv); (void)hipFree(p->w_ctx); (void)hipFree(p->w_hmid);
   (void)hipFree(p->w_act); (void)hipFree(p->w_z); (void)hipFree(p->w_x1);
@@ -412,7 +420,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   }
   const int Rm = c.max_requests;
   for (int i = 0; i < 4; ++i) {
-    CREATE_TRY(hipHostMalloc(&p->h_idx[i], sizeof(int32_t) * 3 * Rm, hipHostMallocDefault));
+    CREATE_TRY(hipHostMalloc(&p->h_idx[i], sizeof(int32_t) * 5 * Rm, hipHostMallocDefault));
     CREATE_TRY(hipEventCreateWithFlags(&p->idx_ev[i], hipEventDisableTiming));
   }
 
@@ -421,7 +429,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   const size_t max_tiles0 = MT / p->tile_m[0] + Rm + 1;
   const size_t max_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + Rm + 1 : 0;
   size_t n_i32 = 3 * (size_t)Rm            // ids, lens, req_slot
-                 + Rm                      // req_tenant
+                 + 3 * (size_t)Rm          // req_tenant, kv_slot, kv_pos
                  + Rm + (Rm + 1)           // perm, tok_off
                  + 2 * (size_t)Rm          // seg_tenant, seg_slot
                  + 2 * ((size_t)Rm + 1)    // seg_req_off, seg_tok_off
@@ -438,7 +446,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   auto take = [&](size_t n) { int32_t* r = q; q += n; return r; };
   Route& rt = p->rt;
   rt.tenant_ids = take(Rm); rt.seq_lens = take(Rm); rt.req_slot = take(Rm);
-  rt.req_tenant = take(Rm);
+  rt.req_tenant = take(Rm); rt.kv_slot = take(Rm); rt.kv_pos = take(Rm);
   rt.perm = take(Rm); rt.tok_off = take(Rm + 1);
   rt.seg_tenant = take(Rm); rt.seg_slot = take(Rm);
   rt.seg_req_off = take(Rm + 1); rt.seg_tok_off = take(Rm + 1);
@@ -671,10 +679,20 @@ int32_t hmi_pool_prefetch(hmi_pool_t* p, int32_t layer, const int32_t* ids, int3
   return HMI_OK;
 }
 
-int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
-                          const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
+namespace {
+enum { KV_NONE = 0, KV_PREFILL = 1, KV_DECODE = 2 };
+}
+
+// The forward of layers [layer_begin, layer_end) over one batch.  kv: KV_PREFILL also stores every
+// row's key and value in the request's cache line seq_slots[r] (from position 0); KV_DECODE takes
+// one row per request (seq_lens == nullptr), appends it to the line and attends over the line.
+static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
+                            const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R, int kv,
+                            const int32_t* seq_slots) {
   if (!p) return HMI_ERR_ARG;
   if (R == 0) return HMI_OK;
+  std::vector<int32_t> ones;
+  if (kv == KV_DECODE && R > 0) { ones.assign(R, 1); seq_lens = ones.data(); }
   if (R < 0 || !x || !y || !tenant_ids || !seq_lens) return fail(p, HMI_ERR_ARG, "null pointer or negative request count");
   if (x == y) return fail(p, HMI_ERR_ARG, "x and y must be different buffers");
   if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
@@ -705,6 +723,19 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
   }
   const int G = (int)p->distinct.size();
   if (G > c.hbm_slots) return fail(p, HMI_ERR_CAPACITY, "%d distinct tenants in one batch > hbm_slots %d", G, c.hbm_slots);
+  if (kv != KV_NONE) {
+    if (!p->d_kv) return fail(p, HMI_ERR_ARG, "no key/value cache: call hmi_kv_create first");
+    if (!seq_slots) return fail(p, HMI_ERR_ARG, "null seq_slots");
+    if (++p->kv_epoch == 0) { std::fill(p->kv_mark.begin(), p->kv_mark.end(), 0u); p->kv_epoch = 1; }
+    for (int r = 0; r < R; ++r) {
+      const int sl = seq_slots[r];
+      if (sl < 0 || sl >= p->kv_seqs) return fail(p, HMI_ERR_ARG, "seq_slots[%d] = %d outside [0,%d)", r, sl, p->kv_seqs);
+      if (p->kv_mark[sl] == p->kv_epoch) return fail(p, HMI_ERR_ARG, "sequence slot %d appears twice in one batch", sl);
+      p->kv_mark[sl] = p->kv_epoch;
+      const int end = kv == KV_PREFILL ? seq_lens[r] : p->kv_len[sl] + 1;
+      if (end > p->kv_max_len) return fail(p, HMI_ERR_SHAPE, "sequence slot %d would hold %d positions > max_len %d", sl, end, p->kv_max_len);
+    }
+  }
   HIP_TRY(p, hipSetDevice(c.device));
 
   // ---- residency of the first layer: hits first (so they cannot be chosen as victims)
@@ -757,6 +788,10 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
     h[r] = tenant_ids[r];
     h[Rm + r] = seq_lens[r];
     h[2 * Rm + r] = p->slot_of_tenant[tenant_ids[r]];
+    if (kv != KV_NONE) {
+      h[3 * Rm + r] = seq_slots[r];
+      h[4 * Rm + r] = kv == KV_PREFILL ? 0 : p->kv_len[seq_slots[r]];
+    }
   }
   hipStream_t s = p->compute;
   // The router reads the three index arrays straight from this pinned (device-mapped) host
@@ -764,6 +799,7 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
   // engine hand-over (about 15 us) on either side.  The event lets the buffer be reused.
   Route rt = p->rt;
   rt.tenant_ids = h; rt.seq_lens = h + Rm; rt.req_slot = h + 2 * Rm;
+  if (kv != KV_NONE) { rt.kv_slot_in = h + 3 * Rm; rt.kv_pos_in = h + 4 * Rm; }
   { ProfSpan ps(p, HMI_KERNEL_ROUTER); launch_router(rt, R, s); }
   HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
   p->last_R = R;
@@ -842,6 +878,14 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
       launch_layernorm(a, p->rt_dense, s);
     };
     auto attention = [&](bool causal) {
+      if (kv != KV_NONE) {   // DEC_PRELN only (checked by the callers)
+        KvArgs k{};
+        k.qkv = p->w_qkv; k.ctx = p->w_ctx; k.d = d; k.n_heads = c.n_heads; k.max_len = p->kv_max_len;
+        k.cache = p->d_kv + (size_t)layer * p->kv_seqs * 2 * (size_t)d * p->kv_max_len;
+        ProfSpan ps(p, HMI_KERNEL_ATTENTION);
+        if (kv == KV_PREFILL) launch_kv_store(k, rt, R, s);
+        else { launch_attn_decode(k, rt, R, s); return; }
+      }
       AttnArgs a{};
       a.qkv = p->w_qkv; a.ctx = p->w_ctx; a.d = d; a.n_heads = c.n_heads; a.causal = causal;
       a.R = R; a.max_len = max_len; a.bf16 = p->bf16; a.n_rows = (int)N;
@@ -929,7 +973,39 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
   HIP_TRY(p, hipGetLastError());
   const uint64_t seq = p->fwd_done.record(s);
   for (int t : p->distinct) p->slot_fwd[p->slot_of_tenant[t]] = seq;
+  if (kv == KV_PREFILL) for (int r = 0; r < R; ++r) p->kv_len[seq_slots[r]] = seq_lens[r];
+  if (kv == KV_DECODE) for (int r = 0; r < R; ++r) p->kv_len[seq_slots[r]] += 1;
   return HMI_OK;
+}
+
+int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
+                          const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
+  return forward_impl(p, layer_begin, layer_end, x, y, tenant_ids, seq_lens, R, KV_NONE, nullptr);
+}
+
+int32_t hmi_kv_create(hmi_pool_t* p, int32_t max_seqs, int32_t max_len) {
+  if (!p) return HMI_ERR_ARG;
+  const hmi_pool_config_t& c = p->cfg;
+  if (c.block != HMI_BLOCK_DEC_PRELN || !p->bf16) return fail(p, HMI_ERR_ARG, "the key/value cache needs a bf16 DEC_PRELN pool");
+  if (p->d_kv) return fail(p, HMI_ERR_ARG, "the pool already has a key/value cache");
+  if (max_seqs < 1 || max_len < 1) return fail(p, HMI_ERR_ARG, "max_seqs and max_len must be positive");
+  HIP_TRY(p, hipSetDevice(c.device));
+  const size_t bytes = (size_t)c.n_layers * max_seqs * 2 * (size_t)c.d_model * max_len * sizeof(uint16_t);
+  HIP_TRY(p, hipMalloc(&p->d_kv, bytes));
+  p->kv_seqs = max_seqs; p->kv_max_len = max_len;
+  p->kv_len.assign(max_seqs, 0);
+  p->kv_mark.assign(max_seqs, 0);
+  return HMI_OK;
+}
+
+int32_t hmi_prefill(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
+                    const int32_t* tenant_ids, const int32_t* seq_lens, const int32_t* seq_slots, int32_t R) {
+  return forward_impl(p, layer_begin, layer_end, x, y, tenant_ids, seq_lens, R, KV_PREFILL, seq_slots);
+}
+
+int32_t hmi_decode_step(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
+                        const int32_t* tenant_ids, const int32_t* seq_slots, int32_t R) {
+  return forward_impl(p, layer_begin, layer_end, x, y, tenant_ids, nullptr, R, KV_DECODE, seq_slots);
 }
 
 int32_t hmi_layer_forward(hmi_pool_t* p, int32_t layer, const void* x, void* y,

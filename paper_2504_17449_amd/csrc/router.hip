@@ -71,6 +71,7 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
       int len = i < R ? rt.seq_lens[i] : 0;
       int tenant = i < R ? rt.tenant_ids[i] : 0;
       slot_r[c] = i < R ? rt.req_slot[i] : 0;
+      if (rt.kv_slot_in && i < R) { rt.kv_slot[i] = rt.kv_slot_in[i]; rt.kv_pos[i] = rt.kv_pos_in[i]; }
       int tot;
       int ex = block_exscan(len, wave_tot, tot) + carry;
       if (i < R) { tok_s[i] = ex; rt.tok_off[i] = ex; rt.req_tenant[i] = tenant; key[0][i] = tenant; val[0][i] = i; }

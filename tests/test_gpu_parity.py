@@ -290,6 +290,65 @@ def test_output_heads_ragged(hmi, dtype, d_model):
         pool.close()
 
 
+def test_decode_steps_with_kv_cache_match_full_causal_forward(hmi):
+    """Prefill ragged prompts of many tenants, then generate: every decode step's row must equal the
+    last row of the oracle's full causal forward over the sequence so far (two layers, so the second
+    layer's cache holds first-layer outputs).  Some requests stop early, so lines of different
+    lengths and a shrinking batch are covered; sequence slots are a scattered subset of the lines."""
+    from paper_2504_17449_amd import harness, HmiError, HMI_ERR_SHAPE, HMI_ERR_ARG
+    from tests.oracle_side import weights_of
+    wl = small(synth.BLOCK_DEC_PRELN, "bf16", n_layers=2, n_tenants=6, hbm_slots=6, n_requests=14, seq_max=70)
+    ids, lens = synth.batch_ids_lens(wl)
+    R, L, G = len(ids), wl.n_layers, 5
+    full = [synth.hidden_states(wl, r, int(lens[r]) + G) for r in range(R)]
+    slots = (np.random.default_rng(1).permutation(R + 5)[:R]).astype(np.int32)
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    wof = [weights_of(wl, l) for l in range(L)]
+
+    def oracle_last_row(r, n_rows):
+        cur = full[r][:n_rows].astype(np.float64)
+        for l in range(L):
+            cur = O.decoder_preln(cur, wof[l](int(ids[r])), wl.n_heads, wl.ln_eps)
+        return cur
+
+    try:
+        harness.load_tenants(pool, wl, sorted(set(ids.tolist())))
+        pool.kv_create(R + 5, int(lens.max()) + G)
+        x = harness.host_to_device(np.concatenate([full[r][:lens[r]] for r in range(R)]), "bf16")
+        y = torch.empty_like(x)
+        pool.prefill(0, L, x, y, ids, lens, slots)
+        torch.cuda.synchronize()
+        y_ref = np.concatenate([oracle_last_row(r, int(lens[r])) for r in range(R)])
+        max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, np.arange(len(y_ref)), "bf16")
+        print(f"  prefill: max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+        assert ok
+        alive = list(range(R))
+        for g in range(G):
+            if g == 2:
+                alive = [r for r in alive if r % 3 != 1]      # a third of the requests stop here
+            if g == 4:
+                alive = alive[::-1]                           # and the batch order changes
+            xn = harness.host_to_device(np.stack([full[r][lens[r] + g] for r in alive]), "bf16")
+            yn = torch.empty_like(xn)
+            pool.decode_step(0, L, xn, yn, ids[alive], slots[alive])
+            torch.cuda.synchronize()
+            want = np.stack([oracle_last_row(r, int(lens[r]) + g + 1)[-1] for r in alive])
+            max_abs, rel, ok = compare(harness.device_to_f64(yn), want, np.arange(len(alive)), "bf16")
+            print(f"  step {g}: {len(alive)} requests, max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+            assert ok, (g, max_abs, rel)
+        # error paths: nothing is enqueued, the line lengths do not move
+        with pytest.raises(HmiError) as e:
+            pool.decode_step(0, L, xn, yn, ids[alive[:2]], slots[[alive[0], alive[0]]])
+        assert e.value.code == HMI_ERR_ARG
+        longest = int(np.argmax(lens))          # its line is full after G steps if it never stopped
+        if longest in alive:
+            with pytest.raises(HmiError) as e:
+                pool.decode_step(0, L, xn[:1], yn[:1], ids[[longest]], slots[[longest]])
+            assert e.value.code == HMI_ERR_SHAPE
+    finally:
+        pool.close()
+
+
 def test_bert_ffn_full_size_sampled(hmi):
     wl = synth.WORKLOADS["bert_ffn"]
     ids, _ = synth.batch_ids_lens(wl)

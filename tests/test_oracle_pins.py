@@ -490,6 +490,18 @@ def test_route_against_rank_count(R, T):
         assert rt["seg_tok_off"][g + 1] - rt["seg_tok_off"][g] == sum(lens[q] for q in members)
 
 
+def test_causal_layer_row_depends_on_earlier_rows_only():
+    """What a decode step with a key/value cache relies on: in the causal pre-LN layer, row i of the
+    output over a whole sequence is the last row of the output over its first i + 1 rows."""
+    d, f, h, S = 8, 16, 2, 9
+    w = enc_weights(3, d, f)
+    x = rnd(4, S, d)
+    full = O.decoder_preln(x, w, h, 1e-5)
+    for i in (0, 3, S - 1):
+        np.testing.assert_allclose(O.decoder_preln(x[:i + 1], w, h, 1e-5)[-1], full[i], rtol=1e-12, atol=1e-13)
+    assert np.abs(O.encoder_postln(x[:4], w, h, 1e-5)[-1] - O.encoder_postln(x, w, h, 1e-5)[3]).max() > 1e-3
+
+
 # ------------------------------------------------------------------ output heads
 
 def test_head_forward_hand_worked():
