@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=256, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--tenants", type=int, default=0, help="override the workload's tenant count (host-tier runs at reduced size)")
     ap.add_argument("--slots", type=int, default=0, help="override the number of HBM slots")
+    ap.add_argument("--decode", type=int, default=0, metavar="G",
+                    help="DEC_PRELN workloads: after the timed steps also prefill the batch into a key/value cache and "
+                         "time G decode steps (one new token per request and step); reported under \"decode\"")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (a kernel of known HBM traffic that "
                          "scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the same run)")
@@ -171,6 +174,34 @@ def main() -> int:
         heads = {"ms_per_call": round(e0.elapsed_time(e1) / args.steps, 5), "predictions": n_pred,
                  "max_classes": wl.max_classes}
 
+    # ---- generation: prefill the same batch into a key/value cache, then G steps of one token per request
+    decode = None
+    if args.decode > 0 and wl.block == synth.BLOCK_DEC_PRELN and wl.dtype == "bf16":
+        G = args.decode
+        R = len(ids)
+        pool.kv_create(R, int(lens.max()) + G + 3)
+        slots = np.arange(R, dtype=np.int32)
+        pool.prefill(0, wl.n_layers, x, y, ids, lens, slots)
+        xn = torch.randn((R, wl.d_model), device="cuda").to(x.dtype)
+        yn = torch.empty_like(xn)
+        for _ in range(3):
+            pool.decode_step(0, wl.n_layers, xn, yn, ids, slots)
+        torch.cuda.synchronize()
+        pool.profile(True)
+        td = time.perf_counter()
+        for _ in range(G):
+            pool.decode_step(0, wl.n_layers, xn, yn, ids, slots)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - td
+        dprof = pool.profile_read()
+        pool.profile(False)
+        weight_bytes = len(set(ids.tolist())) * pool.image_bytes * wl.n_layers
+        kv_bytes = float(lens.sum() + R * (3 + G / 2)) * wl.d_model * 2 * 2 * wl.n_layers
+        decode = {"steps": G, "ms_per_step": round(dt * 1e3 / G, 5), "generated_tokens_per_s": round(R * G / dt, 1),
+                  "algorithmic_GB_per_step": round((weight_bytes + kv_bytes) / 1e9, 3),
+                  "GB_per_s": round((weight_bytes + kv_bytes) / (dt / G) / 1e9, 1),
+                  "kernel_ms_per_step": {k: round(v["ms"] / G, 5) for k, v in dprof.items()}}
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same batch
     cpu = None
     if args.cpu_sample > 0:
@@ -219,6 +250,7 @@ def main() -> int:
             "h2d_GB_per_s": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / elapsed / 1e9, 2),
             "h2d_MB_per_step": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / args.steps / 1e6, 1)},
         "heads": heads,
+        "decode": decode,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -81,6 +81,44 @@ def test_shared_layers_with_adapters_1000_tenants_full_size():
     run_full(synth.WORKLOADS["hbert_shared_adapter"], sample_kw=dict(n_multi=4, n_single=6), heads=True)
 
 
+def test_hgpt_decode_steps_full_size_sampled():
+    """Config 4's batch (256 ragged prompts of up to 512 tokens, 2000 tenants, d = 1024) prefilled into
+    the key/value cache, then three decode steps as bench.py --decode runs them; sampled requests are
+    compared with the oracle's full causal forward over prompt + generated positions."""
+    from paper_2504_17449_amd import harness
+    from tests.oracle_side import weights_of
+    wl = synth.WORKLOADS["hgpt_dec"]
+    ids, lens = synth.batch_ids_lens(wl)
+    R, G = len(ids), 3
+    full = [synth.hidden_states(wl, r, int(lens[r]) + G) for r in range(R)]
+    slots = np.arange(R, dtype=np.int32)[::-1].copy()
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl, sorted(set(ids.tolist())), workers=16)
+        pool.kv_create(R, int(lens.max()) + G)
+        x = harness.host_to_device(np.concatenate([full[r][:lens[r]] for r in range(R)]), "bf16")
+        y = torch.empty_like(x)
+        pool.prefill(0, 1, x, y, ids, lens, slots)
+        outs = []
+        for g in range(G):
+            xn = harness.host_to_device(np.stack([full[r][lens[r] + g] for r in range(R)]), "bf16")
+            yn = torch.empty_like(xn)
+            pool.decode_step(0, 1, xn, yn, ids, slots)
+            outs.append(yn)
+        torch.cuda.synchronize()
+        outs = [harness.device_to_f64(o) for o in outs]
+    finally:
+        pool.close()
+    sample = pick_sample(ids, lens, n_multi=3, n_single=5)
+    wof = weights_of(wl, 0)
+    for g in range(G):
+        want = np.stack([O.decoder_preln(full[r][:lens[r] + g + 1].astype(np.float64), wof(int(ids[r])), wl.n_heads,
+                                         wl.ln_eps)[-1] for r in sample])
+        max_abs, rel, ok = compare(outs[g][sample], want, np.arange(len(sample)), "bf16")
+        print(f"  decode step {g}: {len(sample)} sampled requests, max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+        assert ok, (g, max_abs, rel)
+
+
 # ------------------------------------------------------------------ host tier
 
 class LruModel:
