@@ -176,7 +176,7 @@ def main() -> int:
 
     # ---- generation: prefill the same batch into a key/value cache, then G steps of one token per request
     decode = None
-    if args.decode > 0 and wl.block == synth.BLOCK_DEC_PRELN and wl.dtype == "bf16":
+    if args.decode > 0 and wl.block in (synth.BLOCK_DEC_PRELN, synth.BLOCK_DEC_ADAPTER) and wl.dtype == "bf16":
         G = args.decode
         R = len(ids)
         pool.kv_create(R, int(lens.max()) + G + 3)
@@ -196,6 +196,8 @@ def main() -> int:
         dprof = pool.profile_read()
         pool.profile(False)
         weight_bytes = len(set(ids.tolist())) * pool.image_bytes * wl.n_layers
+        if wl.block == synth.BLOCK_DEC_ADAPTER:   # plus the shared layers, read once per step
+            weight_bytes += wl.n_layers * sum(int(np.prod(sh)) for _, sh, _ in synth.shared_specs(wl)) * 2
         kv_bytes = float(lens.sum() + R * (3 + G / 2)) * wl.d_model * 2 * 2 * wl.n_layers
         decode = {"steps": G, "ms_per_step": round(dt * 1e3 / G, 5), "generated_tokens_per_s": round(R * G / dt, 1),
                   "algorithmic_GB_per_step": round((weight_bytes + kv_bytes) / 1e9, 3),

@@ -56,11 +56,13 @@ enum { HMI_F32 = 0, HMI_BF16 = 1 };
  *               layer shared by all tenants (hmi_pool_load_shared), and per tenant the ADAPTER
  *               tensors with r = adapter_rank, injected after the attention layer:
  *               A = Attn(X);  X1 = LN1(X + A + Up_t(ReLU(Down_t(A))));  Y = LN2(X1 + FFN(X1))
+ *   DEC_ADAPTER the same for decoder-only instances: shared DEC_PRELN tensor set, tenant adapter:
+ *               A = Attn(LN1(X)) causal;  X1 = X + A + Up_t(ReLU(Down_t(A)));  Y = X1 + FFN(LN2(X1))
  * Attention is per request (never across requests), softmax scale 1/sqrt(d/n_heads),
  * packed qkv in q,k,v order, head h owns columns [h*d_head,(h+1)*d_head).  GELU is the
  * exact erf form; LayerNorm uses the biased variance and ln_eps inside the square root. */
 enum { HMI_BLOCK_FFN = 0, HMI_BLOCK_ENC_POSTLN = 1, HMI_BLOCK_DEC_PRELN = 2, HMI_BLOCK_ADAPTER = 3,
-       HMI_BLOCK_ENC_ADAPTER = 4 };
+       HMI_BLOCK_ENC_ADAPTER = 4, HMI_BLOCK_DEC_ADAPTER = 5 };
 
 typedef struct {
   int32_t block;        /* HMI_BLOCK_*                                                    */
@@ -78,7 +80,7 @@ typedef struct {
   float   ln_eps;
   int32_t device;       /* HIP device ordinal                                             */
   void*   compute_stream; /* hipStream_t borrowed from the caller; NULL = default stream  */
-  int32_t adapter_rank; /* ENC_ADAPTER: bottleneck width r of the per-tenant adapter, multiple
+  int32_t adapter_rank; /* ENC_/DEC_ADAPTER: bottleneck width r of the per-tenant adapter, multiple
                            of 64 (bf16) / 16 (f32), <= d_ff; ignored by the other blocks      */
   int32_t max_classes;  /* > 0: tenants may own an output head with up to this many classes
                            (<= 64), see hmi_pool_load_head; 0: no heads                        */
@@ -100,7 +102,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out);
 int32_t hmi_pool_load_tenant(hmi_pool_t* pool, int32_t tenant_id, int32_t layer,
                              const void* const* tensors, int32_t n_tensors);
 
-/* ENC_ADAPTER pools: register the parameters of `layer` that every tenant shares (the
+/* ENC_ADAPTER / DEC_ADAPTER pools: register the parameters of `layer` that every tenant shares (the
  * higher transformer layers stay on the GPU and are reused across tenants, Sec. 3.2.2).
  * `tensors`: HOST array of the 12 ENC_POSTLN tensors as HOST pointers, pool dtype, dense
  * row-major; copied to HBM before return.  Waits for work in flight when it replaces a
@@ -116,7 +118,7 @@ int32_t hmi_pool_load_shared(hmi_pool_t* pool, int32_t layer, const void* const*
  * Errors are detected before anything is enqueued, so y is untouched on error:
  * unknown / unloaded tenant -> HMI_ERR_TENANT; seq_len <= 0, R or N over the configured
  * bound -> HMI_ERR_SHAPE; more distinct tenants than hbm_slots -> HMI_ERR_CAPACITY;
- * ENC_ADAPTER with the layer's shared parameters not loaded -> HMI_ERR_ARG.
+ * ENC_/DEC_ADAPTER with the layer's shared parameters not loaded -> HMI_ERR_ARG.
  * n_requests == 0 is HMI_OK and does nothing. */
 int32_t hmi_layer_forward(hmi_pool_t* pool, int32_t layer, const void* x, void* y,
                           const int32_t* tenant_ids, const int32_t* seq_lens,
@@ -133,7 +135,7 @@ int32_t hmi_stack_forward(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_e
                           const void* x, void* y, const int32_t* tenant_ids,
                           const int32_t* seq_lens, int32_t n_requests);
 
-/* Autoregressive decoding for bf16 DEC_PRELN pools (the paper reports its GPT-style instances in
+/* Autoregressive decoding for bf16 DEC_PRELN and DEC_ADAPTER pools (the paper reports its GPT-style instances in
  * generated tokens per second, Sec. 7): a key/value cache of max_seqs lines ("sequence slots") of
  * max_len positions for every layer of the pool, owned by the library.  Once per pool; other
  * pools -> HMI_ERR_ARG; HMI_ERR_OOM when it does not fit. */

@@ -38,6 +38,7 @@ BLOCK_ENC_POSTLN = 1
 BLOCK_DEC_PRELN = 2
 BLOCK_ADAPTER = 3
 BLOCK_ENC_ADAPTER = 4
+BLOCK_DEC_ADAPTER = 5
 
 
 # --------------------------------------------------------------------------- router
@@ -160,6 +161,16 @@ def encoder_postln_adapter(x, w, n_heads, eps):
     return layer_norm(x1 + ffn(x1, w), w["ln2_g"], w["ln2_b"], eps)
 
 
+def decoder_preln_adapter(x, w, n_heads, eps):
+    """The same task-adapted layer for the paper's decoder-only instances (Sec. 3.2.2 places the
+    adapter after the attention layer of each higher layer; its GPT-style backbone is a pre-LN
+    decoder): a = Attention(LN1(x)) with the causal mask, x1 = x + A(a), y = x1 + FFN(LN2(x1));
+    everything but the adapter A is shared by all tenants."""
+    a = attention(layer_norm(x, w["ln1_g"], w["ln1_b"], eps), w, n_heads, causal=True)
+    x1 = x + adapter_block(a, w)
+    return x1 + ffn(layer_norm(x1, w["ln2_g"], w["ln2_b"], eps), w)
+
+
 def block_forward(block: int, x: np.ndarray, w: Dict[str, np.ndarray], n_heads: int,
                   eps: float) -> np.ndarray:
     """One request's rows through one tenant's block."""
@@ -173,6 +184,8 @@ def block_forward(block: int, x: np.ndarray, w: Dict[str, np.ndarray], n_heads: 
         return adapter_block(x, w)
     if block == BLOCK_ENC_ADAPTER:
         return encoder_postln_adapter(x, w, n_heads, eps)
+    if block == BLOCK_DEC_ADAPTER:
+        return decoder_preln_adapter(x, w, n_heads, eps)
     raise ValueError(f"unknown block {block}")
 
 

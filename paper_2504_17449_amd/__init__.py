@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("HMI_LIB_PATH") or os.path.join(_HERE, "libhmi.so")  #
 HMI_OK, HMI_ERR_ARG, HMI_ERR_OOM, HMI_ERR_TENANT, HMI_ERR_SHAPE, HMI_ERR_CAPACITY, HMI_ERR_DEVICE = \
     0, -1, -2, -3, -4, -5, -6
 HMI_F32, HMI_BF16 = 0, 1
-HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER = 0, 1, 2, 3, 4
+HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER, HMI_BLOCK_DEC_ADAPTER = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward",
            "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_layer_forward", "hmi_stack_forward",

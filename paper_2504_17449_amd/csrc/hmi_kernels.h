@@ -104,6 +104,7 @@ void pack_adapter_operand(void* dst, const void* src, int rows, int cols);
 struct LnArgs {
   const void* in; int in_f32;
   const void* in2;                    // optional second addend in the storage dtype: LN(in + in2)
+  float* sum_out;                     // optional: in + in2 itself, fp32 (the residual stream a pre-LN layer carries on)
   float* out_f32; void* out_st;
   const char* pool; size_t slot_stride; size_t g_off, b_off;
   int d; float eps; int n_rows; int bf16;

@@ -46,6 +46,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a, Route rt) {
                        : reinterpret_cast<const float*>(a.in)[idx];
       if (a.in2) v[i] += BF16 ? bf2f(reinterpret_cast<const uint16_t*>(a.in2)[idx])
                               : reinterpret_cast<const float*>(a.in2)[idx];
+      if (a.sum_out) a.sum_out[idx] = v[i];
       s += v[i];
     }
   }
@@ -110,6 +111,10 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) 
   if (a.in2) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) v[i] += load4(a.in2, row * d + i * 256 + lane * 4, !BF16);
+  }
+  if (a.sum_out) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) *reinterpret_cast<f32x4*>(a.sum_out + row * d + i * 256 + lane * 4) = v[i];
   }
   const int G = rt.n_segments[0];
   for (int i = threadIdx.x; i <= G; i += 256) seg_s[i] = rt.seg_tok_off[i];

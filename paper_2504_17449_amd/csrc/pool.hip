@@ -180,7 +180,8 @@ std::vector<std::pair<int64_t, int64_t>> tensor_shapes(const hmi_pool_config_t& 
       out.push_back({d, 0}); out.push_back({d, 0}); break;
     case HMI_BLOCK_ADAPTER:
       out = ffn; break;
-    case HMI_BLOCK_ENC_ADAPTER: {
+    case HMI_BLOCK_ENC_ADAPTER:
+    case HMI_BLOCK_DEC_ADAPTER: {
       const int64_t r = c.adapter_rank;
       out = {{r, d}, {r, 0}, {d, r}, {d, 0}}; break;
     }
@@ -190,7 +191,7 @@ std::vector<std::pair<int64_t, int64_t>> tensor_shapes(const hmi_pool_config_t& 
 
 // Tensors of the layer that all tenants of an ENC_ADAPTER pool share: an ENC_POSTLN set.
 std::vector<std::pair<int64_t, int64_t>> shared_tensor_shapes(const hmi_pool_config_t& c) {
-  if (c.block != HMI_BLOCK_ENC_ADAPTER) return {};
+  if (c.block != HMI_BLOCK_ENC_ADAPTER && c.block != HMI_BLOCK_DEC_ADAPTER) return {};
   hmi_pool_config_t e = c;
   e.block = HMI_BLOCK_ENC_POSTLN;
   return tensor_shapes(e);
@@ -315,13 +316,14 @@ extern "C" {
 int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   if (!cfg || !out) return fail(nullptr, HMI_ERR_ARG, "null config or out pointer");
   const hmi_pool_config_t& c = *cfg;
-  if (c.block < HMI_BLOCK_FFN || c.block > HMI_BLOCK_ENC_ADAPTER) return fail(nullptr, HMI_ERR_ARG, "bad block %d", c.block);
+  if (c.block < HMI_BLOCK_FFN || c.block > HMI_BLOCK_DEC_ADAPTER) return fail(nullptr, HMI_ERR_ARG, "bad block %d", c.block);
+  const bool composite = c.block == HMI_BLOCK_ENC_ADAPTER || c.block == HMI_BLOCK_DEC_ADAPTER;
   if (c.dtype != HMI_F32 && c.dtype != HMI_BF16) return fail(nullptr, HMI_ERR_ARG, "bad dtype %d", c.dtype);
   const int mult = c.dtype == HMI_BF16 ? 64 : 16;
   if (c.d_model <= 0 || c.d_ff <= 0 || c.d_model % mult || c.d_ff % mult || c.d_model > 2048)
     return fail(nullptr, HMI_ERR_ARG, "d_model/d_ff must be positive multiples of %d (d_model <= 2048)", mult);
-  const bool attn = c.block == HMI_BLOCK_ENC_POSTLN || c.block == HMI_BLOCK_DEC_PRELN || c.block == HMI_BLOCK_ENC_ADAPTER;
-  if (c.block == HMI_BLOCK_ENC_ADAPTER) {
+  const bool attn = c.block == HMI_BLOCK_ENC_POSTLN || c.block == HMI_BLOCK_DEC_PRELN || composite;
+  if (composite) {
     if (c.adapter_rank <= 0 || c.adapter_rank % mult || c.adapter_rank > c.d_ff)
       return fail(nullptr, HMI_ERR_ARG, "adapter_rank must be a positive multiple of %d and <= d_ff", mult);
     if ((int64_t)c.max_tokens > (int64_t)kMaxRequests * kDenseSegRows)
@@ -348,11 +350,11 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   p->esize = p->bf16 ? 2 : 4;
   p->tile_m[0] = p->bf16 ? kBf16TileM0 : kF32TileM;
   p->tile_m[1] = p->bf16 ? kBf16TileM1 : 0;
-  p->rank = c.block == HMI_BLOCK_ENC_ADAPTER ? c.adapter_rank : c.d_ff;
+  p->rank = composite ? c.adapter_rank : c.d_ff;
   // The one-kernel adapter reads and writes the storage dtype: inside the shared layer it always
   // can, as a block of its own only where no fp32 activations pass between layers.
   p->adapter_fused = p->bf16 && adapter_bf16_supported(c.d_model, p->rank) &&
-                     (c.block == HMI_BLOCK_ENC_ADAPTER || (c.block == HMI_BLOCK_ADAPTER && c.n_layers == 1));
+                     (composite || (c.block == HMI_BLOCK_ADAPTER && c.n_layers == 1));
   size_t off = 0;
   for (auto& sh : tensor_shapes(c)) {
     const size_t bytes = (size_t)sh.first * (sh.second ? sh.second : 1) * p->esize;
@@ -436,7 +438,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
                  + MT                      // row_src
                  + 2 * (max_tiles0 + max_tiles1) + 4   // tile lists + counters
                  + kGemmSchedInts;
-  const bool dense = c.block == HMI_BLOCK_ENC_ADAPTER;
+  const bool dense = composite;
   const size_t dense_segs = MT / kDenseSegRows + 2;
   const size_t dense_tiles0 = MT / p->tile_m[0] + 2, dense_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + 2 : 0;
   if (dense) n_i32 += 2 * dense_segs + 1 + MT + 2 * (dense_tiles0 + dense_tiles1);
@@ -576,7 +578,7 @@ int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
 
 int32_t hmi_pool_load_shared(hmi_pool_t* p, int32_t layer, const void* const* tensors, int32_t n_tensors) {
   if (!p) return HMI_ERR_ARG;
-  if (p->cfg.block != HMI_BLOCK_ENC_ADAPTER) return fail(p, HMI_ERR_ARG, "this block kind has no shared parameters");
+  if (p->stl.empty()) return fail(p, HMI_ERR_ARG, "this block kind has no shared parameters");
   if (!tensors) return fail(p, HMI_ERR_ARG, "null tensor list");
   if (layer < 0 || layer >= p->cfg.n_layers) return fail(p, HMI_ERR_ARG, "layer %d outside [0,%d)", layer, p->cfg.n_layers);
   if (n_tensors != (int32_t)p->stl.size()) return fail(p, HMI_ERR_SHAPE, "the shared layer has %d tensors, got %d", (int)p->stl.size(), n_tensors);
@@ -700,7 +702,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
   if (R > p->cfg.max_requests) return fail(p, HMI_ERR_SHAPE, "%d requests > max_requests %d", R, p->cfg.max_requests);
   const hmi_pool_config_t& c = p->cfg;
   const int L = c.n_layers;
-  if (c.block == HMI_BLOCK_ENC_ADAPTER)
+  if (!p->stl.empty())
     for (int l = layer_begin; l < layer_end; ++l)
       if (!p->shared_loaded[l]) return fail(p, HMI_ERR_ARG, "shared parameters of layer %d were never loaded", l);
 
@@ -868,9 +870,10 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       ProfSpan ps(p, HMI_KERNEL_GEMM);
       if (p->bf16) launch_gemm_bf16(g, p->rt_dense, s); else launch_gemm_f32(g, p->rt_dense, s);
     };
-    auto slnorm = [&](const void* in, bool in_f32, const void* in2, float* out_f32, void* out_st, int tg, int tb) {
+    auto slnorm = [&](const void* in, bool in_f32, const void* in2, float* out_f32, void* out_st, int tg, int tb,
+                      float* sum_out = nullptr) {
       LnArgs a{};
-      a.in = in; a.in_f32 = in_f32; a.in2 = in2; a.out_f32 = out_f32; a.out_st = out_st;
+      a.in = in; a.in_f32 = in_f32; a.in2 = in2; a.out_f32 = out_f32; a.out_st = out_st; a.sum_out = sum_out;
       a.pool = p->d_shared; a.slot_stride = 0;
       a.g_off = slay + p->stl[tg].off; a.b_off = slay + p->stl[tb].off;
       a.d = d; a.eps = c.ln_eps; a.n_rows = (int)N; a.bf16 = p->bf16;
@@ -878,7 +881,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       launch_layernorm(a, p->rt_dense, s);
     };
     auto attention = [&](bool causal) {
-      if (kv != KV_NONE) {   // DEC_PRELN only (checked by the callers)
+      if (kv != KV_NONE) {   // decoder blocks only (hmi_kv_create refuses the others)
         KvArgs k{};
         k.qkv = p->w_qkv; k.ctx = p->w_ctx; k.d = d; k.n_heads = c.n_heads; k.max_len = p->kv_max_len;
         k.cache = p->d_kv + (size_t)layer * p->kv_seqs * 2 * (size_t)d * p->kv_max_len;
@@ -891,6 +894,23 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       a.R = R; a.max_len = max_len; a.bf16 = p->bf16; a.n_rows = (int)N;
       ProfSpan ps(p, HMI_KERNEL_ATTENTION);
       launch_attention(a, rt, s);
+    };
+
+    // the tenant's adapter on the attention output: w_act -> w_ctx, tenant route (composite blocks)
+    auto adapter_step = [&]() {
+      const int r = p->rank;
+      if (p->adapter_fused) {
+        AdapterArgs a{};
+        a.X = p->w_act; a.Y = p->w_ctx; a.pool = p->d_pool; a.slot_stride = p->slot_stride;
+        a.wd_off = lay + p->tl[T_W1].off; a.bd_off = lay + p->tl[T_B1].off;
+        a.wu_off = lay + p->tl[T_W2].off; a.bu_off = lay + p->tl[T_B2].off;
+        a.d = d; a.which_tiles = 1; a.n_tiles128 = n_mtiles[1];
+        ProfSpan ps(p, HMI_KERNEL_GEMM);
+        launch_adapter_bf16(a, rt, s);
+      } else {
+        gemm(p->w_act, d, T_W1, T_B1, r, d, EPI_BIAS_RELU, p->w_hmid, r, nullptr, 0, false, false, nullptr);
+        gemm(p->w_hmid, r, T_W2, T_B2, d, r, EPI_BIAS_RESID, p->w_ctx, d, p->w_act, d, f32, f32, nullptr);
+      }
     };
 
     switch (c.block) {
@@ -926,25 +946,26 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
         gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_z, d, p->w_x1, d, true, true, nullptr);
         lnorm(p->w_z, true, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, A_LN2G, A_LN2B);
         break;
+      case HMI_BLOCK_DEC_ADAPTER: {
+        // the decoder-only counterpart: pre-LN, causal, residual stream carried in fp32
+        slnorm(in_res, in_res_f32, nullptr, nullptr, p->w_act, A_LN1G, A_LN1B);
+        sgemm(p->w_act, d, A_WQKV, A_BQKV, 3 * d, d, EPI_BIAS, p->w_qkv, 3 * d, nullptr, 0, false, false);
+        attention(true);
+        sgemm(p->w_ctx, d, A_WO, A_BO, d, d, EPI_BIAS, p->w_act, d, nullptr, 0, false, false);
+        adapter_step();                                                     // w_act -> w_ctx
+        slnorm(in_res, in_res_f32, p->w_ctx, nullptr, p->w_act, A_LN2G, A_LN2B, p->w_x1);   // x1 = x + a', LN2(x1)
+        sgemm(p->w_act, d, A_W1, A_B1, f, d, EPI_BIAS_GELU, p->w_hmid, f, nullptr, 0, false, false);
+        if (last) sgemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, y, d, p->w_x1, d, true, f32);
+        else sgemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_y32, d, p->w_x1, d, true, true);
+        break;
+      }
       case HMI_BLOCK_ENC_ADAPTER: {
         // the shared layer with the tenant's adapter after the attention layer (Sec. 3.2.2):
         // only the adapter step reads per-tenant parameters and follows the tenant route
-        const int r = p->rank;
         sgemm(in_st, d, A_WQKV, A_BQKV, 3 * d, d, EPI_BIAS, p->w_qkv, 3 * d, nullptr, 0, false, false);
         attention(false);
         sgemm(p->w_ctx, d, A_WO, A_BO, d, d, EPI_BIAS, p->w_act, d, nullptr, 0, false, false);
-        if (p->adapter_fused) {
-          AdapterArgs a{};
-          a.X = p->w_act; a.Y = p->w_ctx; a.pool = p->d_pool; a.slot_stride = p->slot_stride;
-          a.wd_off = lay + p->tl[T_W1].off; a.bd_off = lay + p->tl[T_B1].off;
-          a.wu_off = lay + p->tl[T_W2].off; a.bu_off = lay + p->tl[T_B2].off;
-          a.d = d; a.which_tiles = 1; a.n_tiles128 = n_mtiles[1];
-          ProfSpan ps(p, HMI_KERNEL_GEMM);
-          launch_adapter_bf16(a, rt, s);
-        } else {
-          gemm(p->w_act, d, T_W1, T_B1, r, d, EPI_BIAS_RELU, p->w_hmid, r, nullptr, 0, false, false, nullptr);
-          gemm(p->w_hmid, r, T_W2, T_B2, d, r, EPI_BIAS_RESID, p->w_ctx, d, p->w_act, d, f32, f32, nullptr);
-        }
+        adapter_step();                                                     // w_act -> w_ctx
         slnorm(in_res, in_res_f32, p->w_ctx, p->w_x1, p->bf16 ? p->w_act : nullptr, A_LN1G, A_LN1B);
         sgemm(p->bf16 ? (const void*)p->w_act : (const void*)p->w_x1, d, A_W1, A_B1, f, d, EPI_BIAS_GELU,
               p->w_hmid, f, nullptr, 0, false, false);
@@ -986,7 +1007,8 @@ int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end,
 int32_t hmi_kv_create(hmi_pool_t* p, int32_t max_seqs, int32_t max_len) {
   if (!p) return HMI_ERR_ARG;
   const hmi_pool_config_t& c = p->cfg;
-  if (c.block != HMI_BLOCK_DEC_PRELN || !p->bf16) return fail(p, HMI_ERR_ARG, "the key/value cache needs a bf16 DEC_PRELN pool");
+  if ((c.block != HMI_BLOCK_DEC_PRELN && c.block != HMI_BLOCK_DEC_ADAPTER) || !p->bf16)
+    return fail(p, HMI_ERR_ARG, "the key/value cache needs a bf16 DEC_PRELN or DEC_ADAPTER pool");
   if (p->d_kv) return fail(p, HMI_ERR_ARG, "the pool already has a key/value cache");
   if (max_seqs < 1 || max_len < 1) return fail(p, HMI_ERR_ARG, "max_seqs and max_len must be positive");
   HIP_TRY(p, hipSetDevice(c.device));

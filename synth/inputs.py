@@ -24,6 +24,8 @@ BLOCK_DEC_PRELN = 2    # causal attention + FFN, LayerNorm before each sub-layer
 BLOCK_ADAPTER = 3      # Y = X + Up(ReLU(Down(X)))  (bottleneck adapter, Sec. 3.2.2)
 BLOCK_ENC_ADAPTER = 4  # shared post-LN encoder layer + per-tenant adapter after its attention layer (Sec. 3.2.2)
 
+BLOCK_DEC_ADAPTER = 5  # the same with a shared pre-LN causal decoder layer
+
 SHARED = 0x7FFFFFFF    # "tenant" key of the parameters every tenant shares
 
 _TAG_WEIGHT, _TAG_X, _TAG_IDS, _TAG_LENS, _TAG_HEAD = 1, 2, 3, 4, 5
@@ -74,6 +76,10 @@ WORKLOADS = {
     # with the tenant's adapter after its attention layer (Sec. 3.2.2, Sec. 3.3 footnote).
     "hbert_shared_adapter": Workload("hbert_shared_adapter", BLOCK_ENC_ADAPTER, "bf16", 768, 3072, 12, 6, 1000,
                                      512, 128, 128, "zipf", 1.1, 1e-12, 1000, False, adapter_rank=64, max_classes=32),
+    # Its decoder-only counterpart (the paper's GPT-style instances: OPT-125M-shaped higher layers, pre-LN,
+    # causal), prompts of ragged length as in the decoder configuration; generation is timed by bench.py --decode.
+    "hgpt_shared_adapter": Workload("hgpt_shared_adapter", BLOCK_DEC_ADAPTER, "bf16", 768, 3072, 12, 6, 1000,
+                                    256, 32, 512, "zipf", 1.0, 1e-5, 1000, False, adapter_rank=64),
     # Paper-exact bottleneck adapter (Sec. 3.2.2); rank 64 is this build's reading.
     "hbert_adapter": Workload("hbert_adapter", BLOCK_ADAPTER, "bf16", 768, 64, 0, 1, 1000, 512,
                               128, 128, "zipf", 1.1, 0.0, 1000, False),
@@ -88,7 +94,7 @@ def tensor_specs(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
     """
     d, f = wl.d_model, wl.d_ff
     ffn = [("w1", (f, d), "w"), ("b1", (f,), "b"), ("w2", (d, f), "w"), ("b2", (d,), "b")]
-    if wl.block == BLOCK_ENC_ADAPTER:
+    if wl.block in (BLOCK_ENC_ADAPTER, BLOCK_DEC_ADAPTER):
         r = wl.adapter_rank
         return [("w_down", (r, d), "w"), ("b_down", (r,), "b"), ("w_up", (d, r), "w"), ("b_up", (d,), "b")]
     if wl.block == BLOCK_FFN:
@@ -106,9 +112,9 @@ def tensor_specs(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
 
 def shared_specs(wl: Workload) -> List[Tuple[str, Tuple[int, ...], str]]:
     """Tensors of one layer that every tenant shares (BLOCK_ENC_ADAPTER: the encoder layer)."""
-    if wl.block != BLOCK_ENC_ADAPTER:
+    if wl.block not in (BLOCK_ENC_ADAPTER, BLOCK_DEC_ADAPTER):
         return []
-    return tensor_specs(replace(wl, block=BLOCK_ENC_POSTLN))
+    return tensor_specs(replace(wl, block=BLOCK_ENC_POSTLN))   # the decoder layer has the same tensors
 
 
 # ---------------------------------------------------------------- dtype packing

