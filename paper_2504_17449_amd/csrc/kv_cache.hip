@@ -8,9 +8,10 @@
 //
 //   kv_store_kernel    after a full-sequence (prefill) QKV projection: every row's k and v go
 //                      to position (first position of the request + row index) of its line.
-//   attn_decode_kernel one new token per request: one wavefront per (request, head).  Eight
-//                      lanes share a position (16 bytes of the 128-byte key each), eight
-//                      positions per step; an online softmax per lane group, merged at the end.
+//   attn_decode_kernel one new token per request: one workgroup per (request, head).  Eight
+//                      lanes share a position (16 bytes of the 128-byte key each), 32 positions
+//                      per step of the workgroup, four steps' loads in flight at a time; an online
+//                      softmax per lane group, merged at the end.
 //                      The new token's own key and value come from registers and are appended
 //                      to the line for the steps that follow.  All arithmetic in fp32.
 #include "hmi_kernels.h"
@@ -48,27 +49,28 @@ __global__ __launch_bounds__(256) void kv_store_kernel(KvArgs a, Route rt) {
 // running softmax state of one lane: maximum, denominator, 8 numerators
 struct Soft { float m, l, acc[8]; };
 
-__device__ __forceinline__ void soft_add(Soft& s, float score, const float (&v)[8]) {
-  const float mn = fmaxf(s.m, score);
-  const float corr = s.m == mn ? 1.0f : __expf(s.m - mn);
-  const float p = __expf(score - mn);
-  s.l = s.l * corr + p;
+__device__ __forceinline__ void soft_merge(Soft& s, float mo, float lo, const float (&ao)[8]) {
+  const float mn = fmaxf(s.m, mo);
+  const float c0 = s.m == mn ? 1.0f : __expf(s.m - mn), c1 = mo == mn ? 1.0f : __expf(mo - mn);
+  s.l = s.l * c0 + lo * c1;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) s.acc[e] = s.acc[e] * corr + p * v[e];
+  for (int e = 0; e < 8; ++e) s.acc[e] = s.acc[e] * c0 + ao[e] * c1;
   s.m = mn;
 }
 
+constexpr int PB = 4;   // positions a lane group takes per trip (their loads are in flight together)
+
+// One workgroup per (request, head); its 32 lane groups (8 lanes each, 16 bytes of a position's
+// 128-byte key per lane) take positions g, g + 32, ... in batches of PB.
 __global__ __launch_bounds__(256) void attn_decode_kernel(KvArgs a, Route rt) {
-  const int r = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int head = blockIdx.y * 4 + wave;
-  if (head >= a.n_heads) return;
-  const int part = lane & 7, g = lane >> 3;
+  __shared__ float part_s[4][8][10];           // per wavefront and part: m, l, 8 numerators
+  const int r = blockIdx.x, head = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int part = lane & 7, g = wave * 8 + (lane >> 3);
   const int slot = rt.kv_slot[r], pos = rt.kv_pos[r];      // pos = positions already in the line
   const size_t row = (size_t)rt.tok_off[r];
   const uint16_t* qkv = reinterpret_cast<const uint16_t*>(a.qkv) + row * 3 * a.d + head * DH + part * 8;
   const u16x8 q8 = *reinterpret_cast<const u16x8*>(qkv);
-  const u16x8 k8 = *reinterpret_cast<const u16x8*>(qkv + a.d);
-  const u16x8 v8 = *reinterpret_cast<const u16x8*>(qkv + 2 * a.d);
   float q[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) q[e] = bf2f(q8[e]) * 0.125f;   // 1 / sqrt(64)
@@ -79,42 +81,82 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(KvArgs a, Route rt) {
   s.m = -INFINITY; s.l = 0.0f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) s.acc[e] = 0.0f;
-  for (int p = g; p < pos; p += 8) {       // all eight lanes of a group take the same trips
-    const u16x8 kk = *reinterpret_cast<const u16x8*>(Kc + (size_t)p * DH + part * 8);
-    const u16x8 vv = *reinterpret_cast<const u16x8*>(Vc + (size_t)p * DH + part * 8);
-    float sc = 0.0f, vf[8];
+  for (int p0 = g; p0 < pos; p0 += 32 * PB) {   // all eight lanes of a group take the same trips
+    u16x8 kk[PB], vv[PB];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { sc = fmaf(q[e], bf2f(kk[e]), sc); vf[e] = bf2f(vv[e]); }
-    sc += __shfl_xor(sc, 1, 64); sc += __shfl_xor(sc, 2, 64); sc += __shfl_xor(sc, 4, 64);
-    soft_add(s, sc, vf);
-  }
-  {  // the new token itself (every group computes the score, group 0 counts it)
-    float sc = 0.0f, vf[8];
+    for (int u = 0; u < PB; ++u) {
+      const int p = min(p0 + 32 * u, pos - 1);  // surplus positions of the last trip repeat a valid one and get no weight
+      kk[u] = *reinterpret_cast<const u16x8*>(Kc + (size_t)p * DH + part * 8);
+      vv[u] = *reinterpret_cast<const u16x8*>(Vc + (size_t)p * DH + part * 8);
+    }
+    float sc[PB];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { sc = fmaf(q[e], bf2f(k8[e]), sc); vf[e] = bf2f(v8[e]); }
-    sc += __shfl_xor(sc, 1, 64); sc += __shfl_xor(sc, 2, 64); sc += __shfl_xor(sc, 4, 64);
-    if (g == 0) soft_add(s, sc, vf);
-  }
-  // merge the eight groups (lanes with the same part)
+    for (int u = 0; u < PB; ++u) {
+      float t = 0.0f;
 #pragma unroll
-  for (int o = 8; o < 64; o <<= 1) {
-    const float mo = __shfl_xor(s.m, o, 64), lo = __shfl_xor(s.l, o, 64);
-    const float mn = fmaxf(s.m, mo);
-    const float c0 = s.m == mn ? 1.0f : __expf(s.m - mn), c1 = mo == mn ? 1.0f : __expf(mo - mn);
-    s.l = s.l * c0 + lo * c1;
+      for (int e = 0; e < 8; ++e) t = fmaf(q[e], bf2f(kk[u][e]), t);
+      t += __shfl_xor(t, 1, 64); t += __shfl_xor(t, 2, 64); t += __shfl_xor(t, 4, 64);
+      sc[u] = p0 + 32 * u < pos ? t : -INFINITY;
+    }
+    float mn = s.m;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s.acc[e] = s.acc[e] * c0 + __shfl_xor(s.acc[e], o, 64) * c1;
+    for (int u = 0; u < PB; ++u) mn = fmaxf(mn, sc[u]);   // finite: the trip's first position is valid
+    const float corr = s.m == mn ? 1.0f : __expf(s.m - mn);
+    s.l *= corr;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s.acc[e] *= corr;
+#pragma unroll
+    for (int u = 0; u < PB; ++u) {
+      const float w = __expf(sc[u] - mn);                 // exp(-inf) = 0 for the surplus positions
+      s.l += w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s.acc[e] = fmaf(w, bf2f(vv[u][e]), s.acc[e]);
+    }
     s.m = mn;
   }
-  if (g == 0) {
+  // the new token itself, from registers (group 0 counts it and appends it to the line)
+  if (g < 2) {
+    const u16x8 k8 = *reinterpret_cast<const u16x8*>(qkv + a.d);
+    const u16x8 v8 = *reinterpret_cast<const u16x8*>(qkv + 2 * a.d);
+    if (g == 0) {
+      float t = 0.0f, vf[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { t = fmaf(q[e], bf2f(k8[e]), t); vf[e] = bf2f(v8[e]); }
+      t += __shfl_xor(t, 1, 64); t += __shfl_xor(t, 2, 64); t += __shfl_xor(t, 4, 64);
+      soft_merge(s, t, 1.0f, vf);
+      *reinterpret_cast<u16x8*>(Kc + (size_t)pos * DH + part * 8) = k8;
+    } else {
+      *reinterpret_cast<u16x8*>(Vc + (size_t)pos * DH + part * 8) = v8;
+    }
+  }
+  // merge the eight groups of a wavefront (lanes with the same part), then the four wavefronts
+#pragma unroll
+  for (int o = 8; o < 64; o <<= 1) {
+    float ao[8];
+    const float mo = __shfl_xor(s.m, o, 64), lo = __shfl_xor(s.l, o, 64);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ao[e] = __shfl_xor(s.acc[e], o, 64);
+    soft_merge(s, mo, lo, ao);
+  }
+  if (lane < 8) {
+    part_s[wave][part][0] = s.m; part_s[wave][part][1] = s.l;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part_s[wave][part][2 + e] = s.acc[e];
+  }
+  __syncthreads();
+  if (wave == 0 && lane < 8) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      float ao[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ao[e] = part_s[w][part][2 + e];
+      soft_merge(s, part_s[w][part][0], part_s[w][part][1], ao);
+    }
     u16x8 o8;
     const float inv = 1.0f / s.l;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o8[e] = f2bf(s.acc[e] * inv);
     *reinterpret_cast<u16x8*>(reinterpret_cast<uint16_t*>(a.ctx) + row * a.d + head * DH + part * 8) = o8;
-    *reinterpret_cast<u16x8*>(Kc + (size_t)pos * DH + part * 8) = k8;
-  } else if (g == 1) {
-    *reinterpret_cast<u16x8*>(Vc + (size_t)pos * DH + part * 8) = v8;
   }
 }
 
@@ -127,7 +169,7 @@ void launch_kv_store(const KvArgs& a, const Route& rt, int R, hipStream_t s) {
 
 void launch_attn_decode(const KvArgs& a, const Route& rt, int R, hipStream_t s) {
   if (R <= 0) return;
-  hipLaunchKernelGGL(attn_decode_kernel, dim3(R, (a.n_heads + 3) / 4), dim3(256), 0, s, a, rt);
+  hipLaunchKernelGGL(attn_decode_kernel, dim3(R, a.n_heads), dim3(256), 0, s, a, rt);
 }
 
 }  // namespace hmi
