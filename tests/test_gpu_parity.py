@@ -353,6 +353,58 @@ def test_decode_steps_with_kv_cache_match_full_causal_forward(hmi, block):
         pool.close()
 
 
+def test_errors_of_shared_layers_heads_and_cache(hmi):
+    """Every refusal happens before anything is enqueued: y keeps its contents."""
+    from paper_2504_17449_amd import harness
+    wl = small(synth.BLOCK_ENC_ADAPTER, "bf16", n_tenants=3, hbm_slots=3, n_requests=4, seq_max=9, max_classes=4)
+    ids, lens, x = harness.batch_to_device(wl)
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    try:
+        for t in range(3):
+            pool.load_tenant(t, 0, synth.tenant_storage(wl, t, 0))
+        y = torch.full_like(x, 7.0)
+        # shared parameters missing
+        assert hmi.hmi_layer_forward(pool.h, 0, x.data_ptr(), y.data_ptr(), ids, lens) == hmi.HMI_ERR_ARG
+        assert "shared" in hmi.hmi_last_error(pool.h)
+        shared = synth.shared_storage(wl, 0)
+        assert hmi.hmi_pool_load_shared(pool.h, 0, shared[:5]) == hmi.HMI_ERR_SHAPE
+        assert hmi.hmi_pool_load_shared(pool.h, 1, shared) == hmi.HMI_ERR_ARG          # no such layer
+        # heads before any batch was routed, unknown class counts, a tenant without a head
+        labels = torch.zeros(int(lens.sum()), dtype=torch.int32, device=x.device)
+        assert hmi.hmi_head_forward(pool.h, x.data_ptr(), 0, labels.data_ptr()) == hmi.HMI_ERR_ARG
+        w, b = synth.head_tensors(wl, 0, raw=True)
+        assert hmi.hmi_pool_load_head(pool.h, 0, np.zeros((5, wl.d_model), np.uint16), np.zeros(5, np.uint16), False) == hmi.HMI_ERR_SHAPE
+        assert hmi.hmi_pool_load_head(pool.h, 3, w, b, False) == hmi.HMI_ERR_TENANT
+        assert hmi.hmi_pool_load_head(pool.h, 0, w, b, False) == hmi.HMI_OK
+        assert hmi.hmi_pool_load_shared(pool.h, 0, shared) == hmi.HMI_OK
+        torch.cuda.synchronize()
+        assert torch.all(y == 7.0)
+        pool.forward(0, x, y, ids, lens)
+        if len(set(ids.tolist())) > 1 or ids[0] != 0:
+            assert hmi.hmi_head_forward(pool.h, y.data_ptr(), 0, labels.data_ptr()) == hmi.HMI_ERR_TENANT
+        # no key/value cache for encoder pools
+        assert hmi.hmi_kv_create(pool.h, 4, 16) == hmi.HMI_ERR_ARG
+    finally:
+        pool.close()
+    # pools without heads / shared parameters refuse those calls
+    wl2 = small(synth.BLOCK_DEC_PRELN, "bf16", n_tenants=2, hbm_slots=2, n_requests=2, seq_max=5)
+    pool = harness.create_pool(wl2, max_tokens=16)
+    try:
+        assert hmi.hmi_pool_load_shared(pool.h, 0, synth.tenant_storage(wl2, 0, 0)) == hmi.HMI_ERR_ARG
+        assert hmi.hmi_pool_load_head(pool.h, 0, np.zeros((2, 128), np.uint16), np.zeros(2, np.uint16), False) == hmi.HMI_ERR_ARG
+        xs = torch.zeros((2, wl2.d_model), dtype=torch.bfloat16, device="cuda")
+        assert hmi.hmi_decode_step(pool.h, 0, 1, xs.data_ptr(), torch.empty_like(xs).data_ptr(), [0, 1], [0, 1]) == hmi.HMI_ERR_TENANT
+        pool.load_tenant(0, 0, synth.tenant_storage(wl2, 0, 0))
+        pool.load_tenant(1, 0, synth.tenant_storage(wl2, 1, 0))
+        assert hmi.hmi_decode_step(pool.h, 0, 1, xs.data_ptr(), torch.empty_like(xs).data_ptr(), [0, 1], [0, 1]) == hmi.HMI_ERR_ARG   # no cache yet
+        assert hmi.hmi_kv_create(pool.h, 2, 8) == hmi.HMI_OK
+        assert hmi.hmi_kv_create(pool.h, 2, 8) == hmi.HMI_ERR_ARG           # once per pool
+        assert hmi.hmi_decode_step(pool.h, 0, 1, xs.data_ptr(), torch.empty_like(xs).data_ptr(), [0, 1], [0, 2]) == hmi.HMI_ERR_ARG   # slot out of range
+        assert hmi.hmi_prefill(pool.h, 0, 1, xs.data_ptr(), torch.empty_like(xs).data_ptr(), [0], [9], [0]) == hmi.HMI_ERR_SHAPE      # longer than a line
+    finally:
+        pool.close()
+
+
 def test_bert_ffn_full_size_sampled(hmi):
     wl = synth.WORKLOADS["bert_ffn"]
     ids, _ = synth.batch_ids_lens(wl)
