@@ -458,7 +458,17 @@ void launch_dma(const GemmArgs& g, const Route& rt, hipStream_t s) {
 
 void launch_gemm_bf16(const GemmArgs& g0, const Route& rt, hipStream_t s) {
   GemmArgs g = g0;
-  g.which_tiles = 0;                       // all three kernels work on the list of 256-row m-tiles
+  // Few rows per weight matrix (a decode step: at most 32 rows per 128-row tile on average), or a small
+  // launch whose 256 x 256 tiles would occupy under half of the compute units: weight streaming by
+  // many small items instead.
+  const long long tiles256 = (long long)g.n_mtiles_list[0] * ((g.n_out + 255) / 256);
+  if (g.k % 64 == 0 && g.n_out % 32 == 0 && rt.tile_m[1] == 128 && g.n_mtiles_list[1] > 0 && g.n_rows > 0 &&
+      (g.n_rows <= 32LL * g.n_mtiles_list[1] || (tiles256 < 128 && g.n_rows <= 1024))) {
+    g.which_tiles = 1;
+    g.n_mtiles = g.n_mtiles_list[1];
+    return launch_gemm_bf16_skinny(g, rt, s);
+  }
+  g.which_tiles = 0;                       // the other kernels work on the list of 256-row m-tiles
   g.n_mtiles = g.n_mtiles_list[0];
   if (g.n_out % 256 == 0 && g.k % 64 == 0 && g.k >= 192) launch_gemm_bf16_p256(g, rt, s);
   else if (g.n_out % 256 == 0) launch_dma<256, 256, 4, 2, 4>(g, rt, s);

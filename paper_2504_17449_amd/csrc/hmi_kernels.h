@@ -69,6 +69,7 @@ struct GemmArgs {
   const char* pool; size_t slot_stride;  // HBM pool base and bytes per slot
   size_t w_off, b_off;                // byte offsets of W and bias inside a slot (layer included)
   int n_out, k;
+  int n_rows;                         // rows of the whole batch (chooses between the kernels)
   int epi;
   int n_mtiles_list[2];               // exact m-tile counts of both tile lists, computed on the host
   int which_tiles;                    // set by the launcher: index into Route::tile_* ...
@@ -80,6 +81,9 @@ void launch_gemm_f32(const GemmArgs& g, const Route& rt, hipStream_t s);
 // Persistent 256 x 256 tiles, 64-wide k-stages; needs n_out % 256 == 0, k % 64 == 0, k >= 192 and
 // which_tiles / n_mtiles naming the list of 256-row m-tiles.
 void launch_gemm_bf16_p256(const GemmArgs& g, const Route& rt, hipStream_t s);
+// One wavefront per (32 rows, 32 columns) item for launches with few rows per weight matrix; needs
+// k % 64 == 0, n_out % 32 == 0 and which_tiles / n_mtiles naming the list of 128-row m-tiles.
+void launch_gemm_bf16_skinny(const GemmArgs& g, const Route& rt, hipStream_t s);
 constexpr int kBf16TileM0 = 256, kBf16TileM1 = 128;  // heights of the two m-tile lists of bf16 pools
 constexpr int kF32TileM = 64;
 

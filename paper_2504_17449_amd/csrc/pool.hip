@@ -118,6 +118,7 @@ struct hmi_pool {
   std::vector<uint8_t> head_loaded;
   std::vector<int32_t> last_distinct;  // tenants of the last routed batch
   int last_n_mtiles[2] = {0, 0};       // its m-tile counts
+  int last_N = 0;                      // and rows
   float* w_scores = nullptr;           // [max_tokens, kHeadCols] raw scores
 
   // key/value cache for decoding (hmi_kv_create): [layer][sequence slot][k | v][head][position][64] bf16
@@ -634,7 +635,7 @@ int32_t hmi_head_forward(hmi_pool_t* p, const void* h, float* scores, int32_t* l
   g.A = h; g.lda = c.d_model; g.C = p->w_scores; g.ldc = kHeadCols; g.out_f32 = 1;
   g.pool = p->d_heads; g.slot_stride = p->head_stride;
   g.w_off = 0; g.b_off = (size_t)kHeadCols * c.d_model * p->esize;
-  g.n_out = kHeadCols; g.k = c.d_model; g.epi = EPI_BIAS;
+  g.n_out = kHeadCols; g.k = c.d_model; g.n_rows = p->last_N; g.epi = EPI_BIAS;
   g.n_mtiles_list[0] = p->last_n_mtiles[0]; g.n_mtiles_list[1] = p->last_n_mtiles[1];
   g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
   if (p->bf16) launch_gemm_bf16(g, rh, p->compute); else launch_gemm_f32(g, rh, p->compute);
@@ -807,6 +808,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
   p->last_R = R;
   p->last_distinct = p->distinct;
   p->last_n_mtiles[0] = n_mtiles[0]; p->last_n_mtiles[1] = n_mtiles[1];
+  p->last_N = (int)N;
 
   const int d = c.d_model, f = c.d_ff;
   const bool f32 = !p->bf16;  // fp32 pools: "storage" and fp32 coincide
@@ -840,7 +842,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       g.resid_f32 = resid_f32; g.out_f32 = out_f32; g.C2 = C2;
       g.pool = p->d_pool; g.slot_stride = p->slot_stride;
       g.w_off = lay + p->tl[tw].off; g.b_off = lay + p->tl[tb].off;
-      g.n_out = n_out; g.k = k; g.epi = epi; g.n_mtiles_list[0] = n_mtiles[0]; g.n_mtiles_list[1] = n_mtiles[1];
+      g.n_out = n_out; g.k = k; g.n_rows = (int)N; g.epi = epi; g.n_mtiles_list[0] = n_mtiles[0]; g.n_mtiles_list[1] = n_mtiles[1];
       g.which_tiles = 0; g.n_mtiles = n_mtiles[0];
       ProfSpan ps(p, HMI_KERNEL_GEMM);
       if (p->bf16) launch_gemm_bf16(g, rt, s); else launch_gemm_f32(g, rt, s);
@@ -863,7 +865,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       g.resid_f32 = resid_f32; g.out_f32 = out_f32; g.C2 = nullptr;
       g.pool = p->d_shared; g.slot_stride = 0;
       g.w_off = slay + p->stl[tw].off; g.b_off = slay + p->stl[tb].off;
-      g.n_out = n_out; g.k = k; g.epi = epi;
+      g.n_out = n_out; g.k = k; g.n_rows = (int)N; g.epi = epi;
       g.n_mtiles_list[0] = (int)((N + p->tile_m[0] - 1) / p->tile_m[0]);
       g.n_mtiles_list[1] = p->tile_m[1] ? (int)((N + p->tile_m[1] - 1) / p->tile_m[1]) : 0;
       g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
