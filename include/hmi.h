@@ -135,6 +135,20 @@ int32_t hmi_stack_forward(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_e
                           const void* x, void* y, const int32_t* tenant_ids,
                           const int32_t* seq_lens, int32_t n_requests);
 
+/* Representation retrieval, GPU side (Sec. 3.3.1): the hidden states that enter the higher layers
+ * are aggregated from precomputed representations of three-token fragments, one fragment centred
+ * on every token.  table: DEVICE [n_entries, 3, d_model], pool dtype (row e holds the
+ * representations of the first, second and third token of fragment e); frag_ids: DEVICE
+ * int32 [N], the table row of the fragment centred on each token (the lookup itself runs on the
+ * CPU in the paper; ids outside [0, n_entries) are clamped); seq_lens: HOST int32 [n_requests];
+ * x: DEVICE [N, d_model], out.  Token i of a request is the third token of fragment i-1, the
+ * second of fragment i and the first of fragment i+1 where those exist inside the request; x[i]
+ * is the sum of these representations divided by their number (fp32, rounded once).  Enqueued on
+ * compute_stream.  Caller owns table, frag_ids and x. */
+int32_t hmi_plot_aggregate(hmi_pool_t* pool, const void* table, int32_t n_entries,
+                           const int32_t* frag_ids, const int32_t* seq_lens, int32_t n_requests,
+                           void* x);
+
 /* Autoregressive decoding for bf16 DEC_PRELN and DEC_ADAPTER pools (the paper reports its GPT-style instances in
  * generated tokens per second, Sec. 7): a key/value cache of max_seqs lines ("sequence slots") of
  * max_len positions for every layer of the pool, owned by the library.  Once per pool; other

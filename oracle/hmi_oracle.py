@@ -243,3 +243,30 @@ def head_forward(H: np.ndarray, tenant_ids: Sequence[int], seq_lens: Sequence[in
             labels[i] = int(np.argmax(sc))      # first index of the maximum
         start += S
     return scores, labels
+
+
+# --------------------------------------------------------------------------- representation retrieval
+
+def plot_aggregate(table: np.ndarray, frag_ids: Sequence[int], seq_lens: Sequence[int]) -> np.ndarray:
+    """Aggregate of Sec. 3.3.1: the input is swept into three-token fragments X_i = [x_{i-1}, x_i,
+    x_{i+1}], one centred on every token, whose precomputed representations H_i (3 x d) were looked up
+    in the table (``frag_ids[i]`` is the table row of X_i; ``table`` is [entries, 3, d]).  A token's
+    representation is the normalised sum of its representations in the fragments that contain it:
+    token i is the third token of X_{i-1}, the second of X_i and the first of X_{i+1}; fragments do
+    not reach across requests, so the first and last token of a request appear in two fragments (a
+    one-token request in one).  Normalised = divided by the number of summands."""
+    table = np.asarray(table, dtype=np.float64)
+    N = int(np.sum(seq_lens))
+    out = np.zeros((N, table.shape[2]))
+    start = 0
+    for n in seq_lens:
+        n = int(n)
+        for i in range(n):
+            parts = [table[int(frag_ids[start + i]), 1]]
+            if i > 0:
+                parts.append(table[int(frag_ids[start + i - 1]), 2])
+            if i < n - 1:
+                parts.append(table[int(frag_ids[start + i + 1]), 0])
+            out[start + i] = sum(parts) / len(parts)
+        start += n
+    return out

@@ -22,7 +22,7 @@ HMI_F32, HMI_BF16 = 0, 1
 HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER, HMI_BLOCK_DEC_ADAPTER = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward",
-           "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_layer_forward", "hmi_stack_forward",
+           "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_plot_aggregate", "hmi_layer_forward", "hmi_stack_forward",
            "hmi_get_route",
            "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
            "hmi_pool_destroy"]
@@ -59,6 +59,8 @@ def _load() -> C.CDLL:
     lib.hmi_pool_load_head.restype = i32
     lib.hmi_head_forward.argtypes = [vp, vp, vp, vp]
     lib.hmi_head_forward.restype = i32
+    lib.hmi_plot_aggregate.argtypes = [vp, vp, i32, vp, pi32, i32, vp]
+    lib.hmi_plot_aggregate.restype = i32
     lib.hmi_kv_create.argtypes = [vp, i32, i32]
     lib.hmi_kv_create.restype = i32
     lib.hmi_prefill.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, pi32, i32]
@@ -144,6 +146,12 @@ def hmi_pool_load_head(pool: int, tenant_id: int, w: np.ndarray, b: np.ndarray, 
 def hmi_head_forward(pool: int, h_ptr: int, scores_ptr: int, labels_ptr: int) -> int:
     """Device addresses; scores_ptr may be 0."""
     return lib.hmi_head_forward(pool, h_ptr, scores_ptr or None, labels_ptr)
+
+
+def hmi_plot_aggregate(pool: int, table_ptr: int, n_entries: int, frag_ids_ptr: int, seq_lens, x_ptr: int) -> int:
+    """table_ptr / frag_ids_ptr / x_ptr: device addresses; seq_lens: host ints."""
+    lens = _i32(seq_lens)
+    return lib.hmi_plot_aggregate(pool, table_ptr, n_entries, frag_ids_ptr, _p32(lens), lens.shape[0], x_ptr)
 
 
 def hmi_kv_create(pool: int, max_seqs: int, max_len: int) -> int:
@@ -249,6 +257,10 @@ class Pool:
 
     def load_shared(self, layer: int, tensors) -> None:
         self._check(hmi_pool_load_shared(self.h, layer, tensors))
+
+    def plot_aggregate(self, table, frag_ids, seq_lens, x) -> None:
+        """table [entries, 3, d] pool dtype, frag_ids int32 [N], x [N, d]: torch tensors on the device."""
+        self._check(hmi_plot_aggregate(self.h, table.data_ptr(), table.shape[0], frag_ids.data_ptr(), seq_lens, x.data_ptr()))
 
     def kv_create(self, max_seqs: int, max_len: int) -> None:
         self._check(hmi_kv_create(self.h, max_seqs, max_len))

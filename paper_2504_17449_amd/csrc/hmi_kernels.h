@@ -135,6 +135,15 @@ struct AttnArgs {
 };
 void launch_attention(const AttnArgs& a, const Route& rt, hipStream_t s);
 
+// Aggregate of precomputed tri-gram representations: table [n_entries, 3, d] and x [N, d] in the
+// storage dtype, frag_ids [N] device, tok_off [R + 1] (may be pinned host memory).
+struct PlotArgs {
+  const char* table; int n_entries;
+  const int32_t* frag_ids; const int32_t* tok_off;
+  char* x; int d;
+};
+void launch_plot_aggregate(const PlotArgs& a, int R, bool bf16, hipStream_t s);
+
 // Key/value cache of one layer: [slot][k | v][head][position][64] bf16.
 struct KvArgs {
   const void* qkv;     // bf16 [N, 3d] of the batch (q | k | v)

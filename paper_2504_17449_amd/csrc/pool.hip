@@ -646,6 +646,36 @@ int32_t hmi_head_forward(hmi_pool_t* p, const void* h, float* scores, int32_t* l
   return HMI_OK;
 }
 
+int32_t hmi_plot_aggregate(hmi_pool_t* p, const void* table, int32_t n_entries, const int32_t* frag_ids,
+                           const int32_t* seq_lens, int32_t R, void* x) {
+  if (!p) return HMI_ERR_ARG;
+  if (R == 0) return HMI_OK;
+  const hmi_pool_config_t& c = p->cfg;
+  if (R < 0 || !table || !frag_ids || !seq_lens || !x || n_entries < 1) return fail(p, HMI_ERR_ARG, "null pointer, empty table or negative request count");
+  if (R > c.max_requests) return fail(p, HMI_ERR_SHAPE, "%d requests > max_requests %d", R, c.max_requests);
+  int64_t N = 0;
+  for (int r = 0; r < R; ++r) {
+    if (seq_lens[r] <= 0) return fail(p, HMI_ERR_SHAPE, "seq_lens[%d] = %d", r, seq_lens[r]);
+    N += seq_lens[r];
+    if (N > c.max_tokens) return fail(p, HMI_ERR_SHAPE, "batch has more than max_tokens = %d tokens", c.max_tokens);
+  }
+  HIP_TRY(p, hipSetDevice(c.device));
+  // request offsets go through one of the pinned index buffers (the kernel reads them in place)
+  const int bi = p->idx_i;
+  p->idx_i = (p->idx_i + 1) & 3;
+  HIP_TRY(p, hipEventSynchronize(p->idx_ev[bi]));
+  int32_t* h = p->h_idx[bi];
+  h[0] = 0;
+  for (int r = 0; r < R; ++r) h[r + 1] = h[r] + seq_lens[r];
+  PlotArgs a{};
+  a.table = static_cast<const char*>(table); a.n_entries = n_entries; a.frag_ids = frag_ids; a.tok_off = h;
+  a.x = static_cast<char*>(x); a.d = c.d_model;
+  launch_plot_aggregate(a, R, p->bf16, p->compute);
+  HIP_TRY(p, hipEventRecord(p->idx_ev[bi], p->compute));
+  HIP_TRY(p, hipGetLastError());
+  return HMI_OK;
+}
+
 int32_t hmi_pool_prefetch(hmi_pool_t* p, int32_t layer, const int32_t* ids, int32_t n) {
   if (!p) return HMI_ERR_ARG;
   if (n < 0 || (n > 0 && !ids)) return fail(p, HMI_ERR_ARG, "bad tenant list");

@@ -63,7 +63,7 @@ def host_to_device(a32: np.ndarray, dtype: str, device: int = 0) -> torch.Tensor
     raw = synth.to_storage_bytes(a32, dtype)
     if dtype == "bf16":
         return torch.from_numpy(raw.view(np.int16)).view(torch.bfloat16).to(f"cuda:{device}")
-    return torch.from_numpy(raw).to(f"cuda:{device}")
+    return torch.from_numpy(np.array(raw, copy=True)).to(f"cuda:{device}")
 
 
 def device_to_f64(y: torch.Tensor) -> np.ndarray:

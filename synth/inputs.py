@@ -28,7 +28,7 @@ BLOCK_DEC_ADAPTER = 5  # the same with a shared pre-LN causal decoder layer
 
 SHARED = 0x7FFFFFFF    # "tenant" key of the parameters every tenant shares
 
-_TAG_WEIGHT, _TAG_X, _TAG_IDS, _TAG_LENS, _TAG_HEAD = 1, 2, 3, 4, 5
+_TAG_WEIGHT, _TAG_X, _TAG_IDS, _TAG_LENS, _TAG_HEAD, _TAG_PLOT = 1, 2, 3, 4, 5, 6
 _HEAD_LAYER = 1 << 20  # "layer" key of a tenant's output head
 
 
@@ -255,6 +255,19 @@ def head_tensors(wl: Workload, tenant: int, raw: bool = False) -> List[np.ndarra
     c, _ = head_spec(wl, tenant)
     return [_tensor(wl, tenant, _HEAD_LAYER, 0, (c, wl.d_model), "w", raw),
             _tensor(wl, tenant, _HEAD_LAYER, 1, (c,), "b", raw)]
+
+
+def plot_table(wl: Workload, n_entries: int) -> np.ndarray:
+    """Stand-in for the paper's table of precomputed tri-gram representations (Sec. 3.3.1; the real one is
+    built from a corpus): [n_entries, 3, d] ~ N(0, 1), storage-exact fp32."""
+    n = n_entries * 3 * wl.d_model
+    off = _offset(wl.seed, _TAG_PLOT, n_entries, 0, 0, n)
+    return _master(wl.seed, wl.dtype, 1.0)[0][off:off + n].reshape(n_entries, 3, wl.d_model)
+
+
+def plot_fragment_ids(wl: Workload, n_entries: int, n_tokens: int, batch: int = 0) -> np.ndarray:
+    """Table row of the fragment centred on each token of a batch: i.i.d. uniform (the result of the CPU-side lookup)."""
+    return _gen(wl.seed, _TAG_PLOT, batch).integers(0, n_entries, size=n_tokens).astype(np.int32)
 
 
 def hidden_states(wl: Workload, request: int, seq_len: int, batch: int = 0) -> np.ndarray:

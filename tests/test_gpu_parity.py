@@ -405,6 +405,36 @@ def test_errors_of_shared_layers_heads_and_cache(hmi):
         pool.close()
 
 
+@pytest.mark.parametrize("dtype,d_model,entries", [("bf16", 768, 3000), ("bf16", 128, 50), ("f32", 64, 50)])
+def test_plot_aggregate_ragged(hmi, dtype, d_model, entries):
+    """Sec. 3.3.1: token representations aggregated from tri-gram table rows; requests of 1, 2 and more
+    tokens (two or one fragments at the ends), every row compared."""
+    from paper_2504_17449_amd import harness
+    wl = small(synth.BLOCK_FFN, dtype, d_model=d_model, d_ff=d_model, n_requests=40, seq_max=60)
+    _, lens = synth.batch_ids_lens(wl)
+    lens[:3] = [1, 2, 3]
+    N = int(lens.sum())
+    table = synth.plot_table(wl, entries)
+    frag = synth.plot_fragment_ids(wl, entries, N)
+    pool = harness.create_pool(wl, max_tokens=N)
+    try:
+        t_dev = harness.host_to_device(table.reshape(entries * 3, d_model), dtype).reshape(entries, 3, d_model)
+        f_dev = torch.from_numpy(frag).cuda()
+        x = torch.full((N, d_model), 7.0, device="cuda").to(t_dev.dtype)
+        pool.plot_aggregate(t_dev, f_dev, lens, x)
+        torch.cuda.synchronize()
+        got = harness.device_to_f64(x)
+        # refusals leave x alone
+        assert hmi.hmi_plot_aggregate(pool.h, t_dev.data_ptr(), entries, f_dev.data_ptr(), [0, 4], x.data_ptr()) == hmi.HMI_ERR_SHAPE
+        assert hmi.hmi_plot_aggregate(pool.h, 0, entries, f_dev.data_ptr(), lens, x.data_ptr()) == hmi.HMI_ERR_ARG
+    finally:
+        pool.close()
+    want = O.plot_aggregate(table, frag, lens)
+    max_abs, rel, ok = compare(got, want, np.arange(N), dtype)
+    print(f"  aggregate: N={N} max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+    assert ok, (max_abs, rel)
+
+
 def test_bert_ffn_full_size_sampled(hmi):
     wl = synth.WORKLOADS["bert_ffn"]
     ids, _ = synth.batch_ids_lens(wl)

@@ -571,6 +571,32 @@ def test_head_forward_ties_and_brute_force():
     assert O.head_forward(H[:1], [0], [1], lambda t: tie[t], 3)[1].tolist() == [1]
 
 
+# ------------------------------------------------------------------ representation retrieval
+
+def test_plot_aggregate_hand_worked():
+    """Sec. 3.3.1, d = 1.  Table rows (first, second, third token): e0 = (1, 2, 3), e1 = (10, 20, 30),
+    e2 = (100, 200, 300).  One request of three tokens with fragments e0, e1, e2 and one of a single token (e1):
+      token 0: second of e0 and first of e1 -> (2 + 10) / 2 = 6
+      token 1: third of e0, second of e1, first of e2 -> (3 + 20 + 100) / 3 = 41
+      token 2: third of e1 and second of e2 -> (30 + 200) / 2 = 115
+      lone token: second of e1 -> 20"""
+    table = np.array([[[1.0], [2.0], [3.0]], [[10.0], [20.0], [30.0]], [[100.0], [200.0], [300.0]]])
+    np.testing.assert_allclose(O.plot_aggregate(table, [0, 1, 2, 1], [3, 1]), [[6.0], [41.0], [115.0], [20.0]])
+
+
+def test_plot_aggregate_is_a_mean_and_stays_inside_requests():
+    rng = np.random.default_rng(3)
+    d, E = 5, 7
+    const = np.broadcast_to(rng.standard_normal(d), (E, 3, d))     # every representation equal: the mean is that vector
+    ids = rng.integers(0, E, 9)
+    np.testing.assert_allclose(O.plot_aggregate(const, ids, [4, 5]), np.broadcast_to(const[0, 0], (9, d)), atol=1e-15)
+    table = rng.standard_normal((E, 3, d))
+    whole = O.plot_aggregate(table, ids, [4, 5])
+    np.testing.assert_array_equal(whole[:4], O.plot_aggregate(table, ids[:4], [4]))     # requests do not see each other
+    np.testing.assert_array_equal(whole[4:], O.plot_aggregate(table, ids[4:], [5]))
+    assert np.abs(whole - O.plot_aggregate(table, ids, [9])).max() > 1e-3
+
+
 # ------------------------------------------------------------------ the pins do bite
 
 MUTANTS = {
