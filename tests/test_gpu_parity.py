@@ -435,6 +435,39 @@ def test_plot_aggregate_ragged(hmi, dtype, d_model, entries):
     assert ok, (max_abs, rel)
 
 
+@pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_ADAPTER])
+def test_back_to_back_calls_with_different_batches(hmi, block):
+    """Six forward calls enqueued without waiting, alternating between three different batches that
+    share the pool's routing arrays and workspaces: every call's output and the last routing must be
+    right, and the same batch must give the same bits."""
+    from paper_2504_17449_amd import harness
+    wl = small(block, "bf16", d_model=256, d_ff=512, n_heads=4, n_tenants=9, hbm_slots=9, n_requests=25, seq_max=120)
+    batches = [harness.batch_to_device(wl, b) for b in range(3)]
+    pool = harness.create_pool(wl, max_tokens=max(int(l.sum()) for _, l, _ in batches))
+    try:
+        harness.load_tenants(pool, wl)
+        order = [0, 1, 2, 0, 2, 1]
+        outs = []
+        for b in order:
+            ids, lens, x = batches[b]
+            y = torch.empty_like(x)
+            pool.forward(0, x, y, ids, lens)
+            outs.append(y)
+        torch.cuda.synchronize()
+        check_route(pool, batches[order[-1]][0], batches[order[-1]][1])
+        got = [harness.device_to_f64(y) for y in outs]
+    finally:
+        pool.close()
+    refs = {}
+    for b, y in zip(order, got):
+        ids, lens, _ = batches[b]
+        if b not in refs:
+            refs[b] = oracle_forward(wl, ids, lens, None, b)
+        max_abs, rel, ok = compare(y, refs[b], np.arange(len(y)), "bf16")
+        assert ok, (b, max_abs, rel)
+    assert np.array_equal(got[0], got[3]) and np.array_equal(got[1], got[5])    # same batch, same bits
+
+
 def test_bert_ffn_full_size_sampled(hmi):
     wl = synth.WORKLOADS["bert_ffn"]
     ids, _ = synth.batch_ids_lens(wl)
