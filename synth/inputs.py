@@ -76,6 +76,11 @@ WORKLOADS = {
     # with the tenant's adapter after its attention layer (Sec. 3.2.2, Sec. 3.3 footnote).
     "hbert_shared_adapter": Workload("hbert_shared_adapter", BLOCK_ENC_ADAPTER, "bf16", 768, 3072, 12, 6, 1000,
                                      512, 128, 128, "zipf", 1.1, 1e-12, 1000, False, adapter_rank=64, max_classes=32),
+    # The paper's scale claim on its own serving layer (Sec. 7.1: up to 10 000 instances on one GPU): 10 000 tenants'
+    # adapters in pinned host memory (1.2 MB per tenant for six layers), an HBM cache of 2 000 tenants, batches as in
+    # the 10 000-tenant configuration; missing adapters are swapped in on the side stream.
+    "hbert_shared_adapter_10k": Workload("hbert_shared_adapter_10k", BLOCK_ENC_ADAPTER, "bf16", 768, 3072, 12, 6, 10000,
+                                         1024, 16, 256, "zipf", 0.8, 1e-12, 2000, True, adapter_rank=64),
     # Its decoder-only counterpart (the paper's GPT-style instances: OPT-125M-shaped higher layers, pre-LN,
     # causal), prompts of ragged length as in the decoder configuration; generation is timed by bench.py --decode.
     "hgpt_shared_adapter": Workload("hgpt_shared_adapter", BLOCK_DEC_ADAPTER, "bf16", 768, 3072, 12, 6, 1000,

@@ -236,3 +236,40 @@ def test_host_tier_zipf_batches_with_prefetch_bf16():
             assert ok, (b, max_abs, rel)
     finally:
         pool.close()
+
+
+def test_host_tier_adapters_swapped_in_whole():
+    """The 10 000-tenant adapter workload at reduced size: 600 tenants' adapters (three layers, 0.03 MB each)
+    in pinned host memory behind a 64-slot HBM cache under three shared layers.  Images this small are
+    swapped in as one copy of all the tenant's layers; outputs of every batch match the oracle, tenants
+    are evicted, and the copy traffic is a whole number of tenant images."""
+    from paper_2504_17449_amd import harness
+    wl = synth.WORKLOADS["hbert_shared_adapter_10k"].scaled(name="adapter_tier_small", n_tenants=600, hbm_slots=64,
+                                                            n_requests=48, n_layers=3, d_model=256, d_ff=512, n_heads=4,
+                                                            seq_max=80)
+    n_batches = 4
+    batches = [synth.batch_ids_lens(wl, b) for b in range(n_batches)]
+    touched = sorted(set(np.concatenate([b[0] for b in batches]).tolist()) | set(range(wl.hbm_slots)))
+    pool = harness.create_pool(wl, max_tokens=wl.n_requests * wl.seq_max)
+    try:
+        harness.load_tenants(pool, wl, touched, workers=8)
+        outs = []
+        for b in range(n_batches):
+            ids, lens, x = harness.batch_to_device(wl, b)
+            y = torch.empty_like(x)
+            pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
+            if b + 1 < n_batches:
+                pool.prefetch(0, batches[b + 1][0])
+            outs.append((ids, lens, y))
+        torch.cuda.synchronize()
+        st = pool.stats()
+        print(f"  stats {st}", flush=True)
+        assert st["misses"] > 0 and st["evictions"] > 0
+        assert st["bytes_h2d"] > 0 and st["bytes_h2d"] % (pool.image_bytes * wl.n_layers) == 0
+        for b, (ids, lens, y) in enumerate(outs):
+            y_ref = oracle_forward(wl, ids, lens, None, batch=b)
+            max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, np.arange(len(y_ref)), wl.dtype)
+            print(f"  batch {b}: max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+            assert ok, (b, max_abs, rel)
+    finally:
+        pool.close()
