@@ -273,3 +273,34 @@ def test_host_tier_adapters_swapped_in_whole():
             assert ok, (b, max_abs, rel)
     finally:
         pool.close()
+
+
+def test_adapter_kernel_at_the_request_limit_more_units_than_a_workgroup_lists():
+    """2 048 requests (the router's limit) of 200-400 rows: over 600 000 rows = more than 16 384 units of 32 rows,
+    so the one-kernel adapter launches more workgroups than compute units (a workgroup lists at most 64 units).
+    Routing bit-exact, sampled requests against the oracle, all other rows finite."""
+    from paper_2504_17449_amd import harness
+    wl = synth.Workload("adapter_limit", synth.BLOCK_ADAPTER, "bf16", 256, 64, 0, 1, 50, 2048, 200, 400,
+                        "zipf", 1.0, 0.0, 50, False, seed=4)
+    ids, lens, x = harness.batch_to_device(wl)
+    N = int(lens.sum())
+    assert N > 32 * 64 * 256
+    pool = harness.create_pool(wl, max_tokens=N)
+    try:
+        harness.load_tenants(pool, wl)
+        y = torch.empty_like(x)
+        pool.forward(0, x, y, ids, lens)
+        torch.cuda.synchronize()
+        check_route(pool, ids, lens)
+        y_gpu = harness.device_to_f64(y)
+    finally:
+        pool.close()
+    sample = pick_sample(ids, lens, n_multi=6, n_single=8) + [0, len(ids) - 1]
+    y_ref = oracle_forward(wl, ids, lens, sample)
+    max_abs, rel, ok = compare(y_gpu, y_ref, rows_of(lens, sorted(set(sample))), wl.dtype)
+    print(f"  N={N} sampled {len(set(sample))} requests: max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+    assert ok, (max_abs, rel)
+    assert np.isfinite(y_gpu).all()
+    # the adapter moves every row a little: no row was left as x or skipped
+    x64 = harness.device_to_f64(x)
+    assert (np.abs(y_gpu - x64).max(axis=1) > 0).all()
