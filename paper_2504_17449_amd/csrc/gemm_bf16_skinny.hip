@@ -4,10 +4,10 @@
 // is cut into many small independent items that keep every compute unit's memory pipe full:
 //
 //   item = (32 rows of one segment) x (32 output columns) x (all of k), one WAVEFRONT per item,
-//   six items per workgroup, no workgroup barriers.
+//   five items per workgroup, no workgroup barriers.
 //
 // A wavefront streams its 32 weight rows and its 32 activation rows (gathered through row_src) through a
-// private LDS ring of three stages of 64 k (direct-to-LDS copies of full 128-byte lines, two stages in
+// private LDS ring of four stages of 64 k (direct-to-LDS copies of full 128-byte lines, three stages in
 // flight), reads the weights back as MFMA first operands in the permuted row order that gives a lane 16
 // consecutive output columns of one row, and the activations as second operands.  Items of the four row
 // blocks of one 128-row tile are neighbours, so a weight panel that several row blocks need is fetched
@@ -29,10 +29,10 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 constexpr int SK = 32;                    // rows and columns of an item
-constexpr int STAGES = 3, STAGE_BYTES = SK * 128;          // per operand: 32 rows of 64 k
+constexpr int STAGES = 4, STAGE_BYTES = SK * 128;          // per operand: 32 rows of 64 k
 constexpr int X_RING = STAGES * STAGE_BYTES;               // a wavefront's ring: weight stages, then activation stages
 constexpr int WAVE_LDS = 2 * STAGES * STAGE_BYTES;
-constexpr int WAVES = 6, LDS_BYTES = WAVES * WAVE_LDS;     // 144 KB
+constexpr int WAVES = 5, LDS_BYTES = WAVES * WAVE_LDS;     // 160 KB
 
 #define HMI_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g
   const int fw_base = rw * 128 + ((lh ^ swz_w(rw)) << 4);
   const int fx_base = X_RING + l32 * 128 + ((lh ^ swz_a(l32)) << 4);
 
-  // stage S of both operands into ring slot S mod 3 (8 copies); past the end: an in-bounds re-read nobody consumes
+  // stage S of both operands into ring slot S mod 4 (8 copies); past the end: an in-bounds re-read nobody consumes
 #define HMI_COPY_STAGE(S)                                                                          \
   {                                                                                                \
     const int st_ = min((S), KT - 1);                                                              \
@@ -115,8 +115,9 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g
 
   HMI_COPY_STAGE(0)
   HMI_COPY_STAGE(1)
+  HMI_COPY_STAGE(2)
   for (int s = 0; s < KT; ++s) {
-    HMI_WAIT_VMCNT(8);                       // stage s has landed; the 8 copies of stage s + 1 may be in flight
+    HMI_WAIT_VMCNT(16);                      // stage s has landed; the 16 copies of stages s + 1, s + 2 may be in flight
     __builtin_amdgcn_sched_barrier(0);
     const unsigned char* sb = ring + (s % STAGES) * STAGE_BYTES;
     bf16x8 fw[4], fx[4];
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks], fx[ks], acc, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    HMI_COPY_STAGE(s + 2)                    // into the slot that stage s - 1 was read from
+    HMI_COPY_STAGE(s + 3)                    // into the slot that stage s - 1 was read from
   }
 #undef HMI_COPY_STAGE
   HMI_WAIT_VMCNT(0);                         // the trailing copies must have landed before the LDS is handed on
