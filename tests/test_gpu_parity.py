@@ -468,6 +468,32 @@ def test_back_to_back_calls_with_different_batches(hmi, block):
     assert np.array_equal(got[0], got[3]) and np.array_equal(got[1], got[5])    # same batch, same bits
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_small_shapes(hmi, seed):
+    """Shapes nobody picked by hand: block kind, widths, ranks, head counts, layer counts, request counts and
+    length ranges drawn from a seeded generator (bf16; every row compared).  Small batches take the skinny GEMM,
+    larger ones the tiled kernels, widths of 256 / 512 / 768 the one-kernel adapter."""
+    rng = np.random.default_rng(1000 + seed)
+    block = int(rng.choice([synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN, synth.BLOCK_ADAPTER,
+                            synth.BLOCK_ENC_ADAPTER, synth.BLOCK_DEC_ADAPTER]))
+    heads = int(rng.integers(1, 7))
+    attn = block not in (synth.BLOCK_FFN, synth.BLOCK_ADAPTER)
+    d = heads * 64 if attn else int(rng.integers(1, 13)) * 64
+    f = 64 if block == synth.BLOCK_ADAPTER else int(rng.integers(1, 9)) * 64
+    tenants = int(rng.integers(1, 10))
+    smax = int(rng.choice([1, 7, 40, 150, 330]))
+    kw = dict(d_model=d, d_ff=f, n_heads=heads if attn else 0, n_layers=int(rng.integers(1, 4)), n_tenants=tenants,
+              hbm_slots=tenants, n_requests=int(rng.integers(1, 30)), seq_min=1, seq_max=smax,
+              popularity=str(rng.choice(["uniform", "zipf"])), seed=int(rng.integers(0, 1000)))
+    if block in (synth.BLOCK_ENC_ADAPTER, synth.BLOCK_DEC_ADAPTER):
+        kw["adapter_rank"] = int(rng.choice([64, 128]))
+        kw["d_ff"] = max(f, kw["adapter_rank"])
+    if block in (synth.BLOCK_DEC_PRELN, synth.BLOCK_DEC_ADAPTER):
+        kw["n_layers"] = min(kw["n_layers"], 2)      # pre-LN stacks carry |y| upwards: keep it under the bf16 half-ulp bar
+    print(f"seed {seed}: block {block} {kw}", flush=True)
+    run_case(hmi, small(block, "bf16", **kw))
+
+
 def test_bert_ffn_full_size_sampled(hmi):
     wl = synth.WORKLOADS["bert_ffn"]
     ids, _ = synth.batch_ids_lens(wl)
