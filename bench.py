@@ -174,6 +174,32 @@ def main() -> int:
         heads = {"ms_per_call": round(e0.elapsed_time(e1) / args.steps, 5), "predictions": n_pred,
                  "max_classes": wl.max_classes}
 
+    # ---- the paper's whole GPU-side request path on this workload: Aggregate of looked-up tri-gram
+    #      representations -> the layer stack -> the tenants' output heads (reported beside the step)
+    pipeline = None
+    if wl.max_classes and not wl.host_tier:
+        entries = 5000
+        table = harness.host_to_device(synth.plot_table(wl, entries).reshape(entries * 3, wl.d_model), wl.dtype)
+        table = table.reshape(entries, 3, wl.d_model)
+        frag = torch.from_numpy(synth.plot_fragment_ids(wl, entries, N)).cuda()
+        xin = torch.empty_like(x)
+
+        def request_path():
+            pool.plot_aggregate(table, frag, lens, xin)
+            pool.stack_forward(0, wl.n_layers, xin, y, ids, lens)
+            pool.head_forward(y, None, labels)
+
+        for _ in range(3):
+            request_path()
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
+        for _ in range(args.steps):
+            request_path()
+        torch.cuda.synchronize()
+        dtp = (time.perf_counter() - tp) / args.steps
+        pipeline = {"what": "aggregate + all layers + heads", "ms_per_batch": round(dtp * 1e3, 4),
+                    "requests_per_s": round(len(ids) / dtp, 1), "tokens_per_s": round(N / dtp, 1)}
+
     # ---- generation: prefill the same batch into a key/value cache, then G steps of one token per request
     decode = None
     if args.decode > 0 and wl.block in (synth.BLOCK_DEC_PRELN, synth.BLOCK_DEC_ADAPTER) and wl.dtype == "bf16":
@@ -253,6 +279,7 @@ def main() -> int:
             "h2d_MB_per_step": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / args.steps / 1e6, 1)},
         "heads": heads,
         "decode": decode,
+        "request_path": pipeline,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
