@@ -68,17 +68,30 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, Route rt) {
 
   for (int k0 = 0; k0 < n_keys; k0 += KB) {
     __syncthreads();  // previous block fully consumed
-    // stage K (swizzled 16-byte chunks) and V^T; 64 keys x 8 chunks = 512 chunks, 2 per thread
+    // stage K (swizzled 16-byte chunks): 64 keys x 8 chunks = 512 chunks, 2 per thread
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int qd = t + 256 * i, key = qd >> 3, c = qd & 7;
       const int kr = min(k0 + key, len - 1);
       const uint4 kv = *reinterpret_cast<const uint4*>(Kg + (size_t)kr * ld + c * 8);
       *reinterpret_cast<uint4*>(Ks + key * DH + ((c ^ swz(key)) << 3)) = kv;
-      const uint4 vv = *reinterpret_cast<const uint4*>(Vg + (size_t)kr * ld + c * 8);
-      const uint16_t* ve = reinterpret_cast<const uint16_t*>(&vv);
+    }
+    // stage V^T: thread (key group kg, column pair cp) reads two columns of eight keys (4 bytes per
+    // key, a wavefront's 32 column pairs cover the key's 128-byte row) and writes each column's eight
+    // keys as one 16-byte piece
+    {
+      const int kg = t >> 5, cp = t & 31;
+      uint32_t w[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * VT_LD + key] = ve[e];
+      for (int e = 0; e < 8; ++e)
+        w[e] = *reinterpret_cast<const uint32_t*>(Vg + (size_t)min(k0 + kg * 8 + e, len - 1) * ld + cp * 2);
+      uint4 lo, hi;
+      lo.x = (w[0] & 0xFFFFu) | (w[1] << 16); hi.x = (w[0] >> 16) | (w[1] & 0xFFFF0000u);
+      lo.y = (w[2] & 0xFFFFu) | (w[3] << 16); hi.y = (w[2] >> 16) | (w[3] & 0xFFFF0000u);
+      lo.z = (w[4] & 0xFFFFu) | (w[5] << 16); hi.z = (w[4] >> 16) | (w[5] & 0xFFFF0000u);
+      lo.w = (w[6] & 0xFFFFu) | (w[7] << 16); hi.w = (w[6] >> 16) | (w[7] & 0xFFFF0000u);
+      *reinterpret_cast<uint4*>(Vt + (2 * cp) * VT_LD + kg * 8) = lo;
+      *reinterpret_cast<uint4*>(Vt + (2 * cp + 1) * VT_LD + kg * 8) = hi;
     }
     __syncthreads();
     const bool skip = !wave_has_rows || (a.causal && k0 > wave_q_last);
