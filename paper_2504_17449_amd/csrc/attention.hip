@@ -4,7 +4,8 @@
 // forward (Sec. 6.3 gives the batching, BERT / GPT give the sub-layer).
 //
 // bf16 kernel (d_head = 64), one workgroup = 128 query rows of one (request, head), four
-// wavefronts of 32 queries each.  Keys/values stream through LDS in blocks of 64 keys with
+// wavefronts of 32 queries each.  Keys/values stream through LDS in blocks of 64 keys (the next
+// block is loaded into registers while this one is multiplied; V is transposed in registers) with
 // an online softmax.  Both products run on v_mfma_f32_32x32x16_bf16 in TRANSPOSED form so
 // that every lane owns one query column throughout:
 //   S^T = K Q^T   (A = K block from LDS, B = Q^T held in registers)
@@ -66,33 +67,43 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, Route rt) {
   const bool wave_has_rows = q0 + wave * 32 < len;
   const float scale = 0.125f;                                  // 1/sqrt(64)
 
+  // A key block goes global -> registers -> LDS; the registers of the next block are loaded while this
+  // one is multiplied.  K: 64 keys x 8 chunks of 16 bytes, two per thread, swizzled.  V^T: thread (key
+  // group kg, column pair cp) reads two columns of eight keys (4 bytes per key, a wavefront's 32 column
+  // pairs cover the key's 128-byte row) and writes each column's eight keys as one 16-byte piece.
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 kreg[2];
+  uint32_t vw[8];
+  const int v_kg = t >> 5, v_cp = t & 31;
+#define HMI_LOAD_BLOCK(K0)                                                                         \
+  {                                                                                                \
+    _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                \
+      const int qd = t + 256 * i, key = qd >> 3, c = qd & 7;                                       \
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kg + (size_t)min((K0) + key, len - 1) * ld + c * 8); \
+    }                                                                                              \
+    _Pragma("unroll") for (int e = 0; e < 8; ++e)                                                  \
+      vw[e] = *reinterpret_cast<const uint32_t*>(Vg + (size_t)min((K0) + v_kg * 8 + e, len - 1) * ld + v_cp * 2); \
+  }
+  HMI_LOAD_BLOCK(0)
+
   for (int k0 = 0; k0 < n_keys; k0 += KB) {
     __syncthreads();  // previous block fully consumed
-    // stage K (swizzled 16-byte chunks): 64 keys x 8 chunks = 512 chunks, 2 per thread
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int qd = t + 256 * i, key = qd >> 3, c = qd & 7;
-      const int kr = min(k0 + key, len - 1);
-      const uint4 kv = *reinterpret_cast<const uint4*>(Kg + (size_t)kr * ld + c * 8);
-      *reinterpret_cast<uint4*>(Ks + key * DH + ((c ^ swz(key)) << 3)) = kv;
+      *reinterpret_cast<u32x4*>(Ks + key * DH + ((c ^ swz(key)) << 3)) = kreg[i];
     }
-    // stage V^T: thread (key group kg, column pair cp) reads two columns of eight keys (4 bytes per
-    // key, a wavefront's 32 column pairs cover the key's 128-byte row) and writes each column's eight
-    // keys as one 16-byte piece
     {
-      const int kg = t >> 5, cp = t & 31;
-      uint32_t w[8];
+      u32x4 lo, hi;
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        w[e] = *reinterpret_cast<const uint32_t*>(Vg + (size_t)min(k0 + kg * 8 + e, len - 1) * ld + cp * 2);
-      uint4 lo, hi;
-      lo.x = (w[0] & 0xFFFFu) | (w[1] << 16); hi.x = (w[0] >> 16) | (w[1] & 0xFFFF0000u);
-      lo.y = (w[2] & 0xFFFFu) | (w[3] << 16); hi.y = (w[2] >> 16) | (w[3] & 0xFFFF0000u);
-      lo.z = (w[4] & 0xFFFFu) | (w[5] << 16); hi.z = (w[4] >> 16) | (w[5] & 0xFFFF0000u);
-      lo.w = (w[6] & 0xFFFFu) | (w[7] << 16); hi.w = (w[6] >> 16) | (w[7] & 0xFFFF0000u);
-      *reinterpret_cast<uint4*>(Vt + (2 * cp) * VT_LD + kg * 8) = lo;
-      *reinterpret_cast<uint4*>(Vt + (2 * cp + 1) * VT_LD + kg * 8) = hi;
+      for (int j = 0; j < 4; ++j) {
+        lo[j] = (vw[2 * j] & 0xFFFFu) | (vw[2 * j + 1] << 16);
+        hi[j] = (vw[2 * j] >> 16) | (vw[2 * j + 1] & 0xFFFF0000u);
+      }
+      *reinterpret_cast<u32x4*>(Vt + (2 * v_cp) * VT_LD + v_kg * 8) = lo;
+      *reinterpret_cast<u32x4*>(Vt + (2 * v_cp + 1) * VT_LD + v_kg * 8) = hi;
     }
+    if (k0 + KB < n_keys) HMI_LOAD_BLOCK(k0 + KB)   // in flight during this block's arithmetic
     __syncthreads();
     const bool skip = !wave_has_rows || (a.causal && k0 > wave_q_last);
     if (skip) continue;
@@ -164,6 +175,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, Route rt) {
         }
       }
   }
+
+#undef HMI_LOAD_BLOCK
 
   // ---- normalise and store: o[u][i] is dh = u*32 + 8*(i/4) + 4*lh + i%4 of query q
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
