@@ -304,3 +304,41 @@ def test_adapter_kernel_at_the_request_limit_more_units_than_a_workgroup_lists()
     # the adapter moves every row a little: no row was left as x or skipped
     x64 = harness.device_to_f64(x)
     assert (np.abs(y_gpu - x64).max(axis=1) > 0).all()
+
+
+def test_ten_thousand_tenants_adapters_behind_the_host_tier_full_size():
+    """bench.py --workload hbert_shared_adapter_10k as it is timed: all 10 000 tenants' six-layer adapters in pinned
+    host memory, 2 000 HBM slots, two consecutive Zipf batches of 1 024 ragged requests with the second one's tenants
+    prefetched during the first; sampled requests of both batches against the oracle, routing bit-exact."""
+    from paper_2504_17449_amd import harness
+    wl = synth.WORKLOADS["hbert_shared_adapter_10k"]
+    t0 = time.time()
+    pool = harness.create_pool(wl, max_tokens=wl.n_requests * wl.seq_max)
+    try:
+        harness.load_tenants(pool, wl, workers=16)
+        print(f"{wl.name}: {wl.n_tenants} tenants x {wl.n_layers} layers in pinned memory, {time.time() - t0:.1f}s", flush=True)
+        batches = [synth.batch_ids_lens(wl, b) for b in range(2)]
+        outs = []
+        for b in range(2):
+            ids, lens, x = harness.batch_to_device(wl, b)
+            y = torch.empty_like(x)
+            pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
+            if b == 0:
+                for layer in range(wl.n_layers):
+                    pool.prefetch(layer, np.unique(batches[1][0]))
+            outs.append((ids, lens, y))
+        torch.cuda.synchronize()
+        check_route(pool, batches[1][0], batches[1][1])
+        st = pool.stats()
+        print(f"  stats {st}", flush=True)
+        assert st["misses"] > 100 and st["evictions"] > 0
+        got = [harness.device_to_f64(y) for _, _, y in outs]
+    finally:
+        pool.close()
+    for b, ((ids, lens, _), y) in enumerate(zip(outs, got)):
+        sample = pick_sample(ids, lens, n_multi=3, n_single=5)
+        y_ref = oracle_forward(wl, ids, lens, sample, batch=b)
+        max_abs, rel, ok = compare(y, y_ref, rows_of(lens, sample), wl.dtype)
+        print(f"  batch {b}: {len(sample)} requests max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+        assert ok, (b, max_abs, rel)
+        assert np.isfinite(y).all()
