@@ -6,6 +6,11 @@
 //   item = (32 rows of one segment) x (32 output columns) x (all of k), one WAVEFRONT per item,
 //   five items per workgroup, no workgroup barriers.
 //
+// A launch with so few items that they would not even give every compute unit one workgroup (a decode
+// step through parameters that all tenants share: a few hundred rows in all) is bound by the latency of
+// one wavefront's walk over k instead; there an item goes to a workgroup of four wavefronts that take
+// a quarter of k each and add their partial sums through LDS in a fixed order.
+//
 // A wavefront streams its 32 weight rows and its 32 activation rows (gathered through row_src) through a
 // private LDS ring of four stages of 64 k (direct-to-LDS copies of full 128-byte lines, three stages in
 // flight), reads the weights back as MFMA first operands in the permuted row order that gives a lane 16
@@ -33,6 +38,8 @@ constexpr int STAGES = 4, STAGE_BYTES = SK * 128;          // per operand: 32 ro
 constexpr int X_RING = STAGES * STAGE_BYTES;               // a wavefront's ring: weight stages, then activation stages
 constexpr int WAVE_LDS = 2 * STAGES * STAGE_BYTES;
 constexpr int WAVES = 5, LDS_BYTES = WAVES * WAVE_LDS;     // 160 KB
+constexpr int KSPLIT = 4;                                  // wavefronts that share the k of one item in the split variant
+constexpr int kSplitMaxItems = 384;                        // measured: 192 items 25 -> 9 us per launch, 576 and 768 items slower with it
 
 #define HMI_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
@@ -55,11 +62,16 @@ __device__ __forceinline__ int perm_w(int i) { return ((i >> 2) & 1) * 16 + (i >
 // row_split: an item is one 32-row block of a 128-row tile (launches with full tiles but few of them);
 // otherwise an item is a whole tile and its wavefront takes the tile's row blocks one after the other
 // (decode steps: nearly every tile holds a single, short row block).
-__global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g, Route rt, int n_items, int row_split) {
+//
+// SPLIT: the workgroup is KSPLIT wavefronts that share one item (row_split items only); wavefront w
+// multiplies the w-th quarter of k.  Everything that decides whether a wavefront leaves early is the same
+// for the whole workgroup, so all of them reach the barrier in front of the sum.
+template <bool SPLIT>
+__global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinny_kernel(GemmArgs g, Route rt, int n_items, int row_split) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int item = blockIdx.x * WAVES + wave;
+  const int item = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * WAVES + wave;
   if (item >= n_items) return;
   // item = (tile * NB + column block) [* 4 + row block of the 128-row tile]
   const int NB = g.n_out / SK;
@@ -78,7 +90,9 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g
   const char* Wp = g.pool + slot_base + g.w_off + (size_t)n0 * kb;
   const char* Ap = reinterpret_cast<const char*>(g.A);
   const int l32 = lane & 31, lh = lane >> 5;
-  const int KT = g.k / 64;
+  // this wavefront's stages of k: all of them, or its quarter
+  const int KT = SPLIT ? g.k / 64 / KSPLIT : g.k / 64;
+  const int k_first = SPLIT ? wave * KT : 0;
 
   // copies: instruction i moves rows 8 i .. 8 i + 7 of a stage; lane l fills position (row 8 i + l / 8,
   // chunk l % 8) with the row's chunk (l % 8) ^ swizzle(row).  Rows past the end of a short row block
@@ -99,7 +113,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g
   // stage S of both operands into ring slot S mod 4 (8 copies); past the end: an in-bounds re-read nobody consumes
 #define HMI_COPY_STAGE(S)                                                                          \
   {                                                                                                \
-    const int st_ = min((S), KT - 1);                                                              \
+    const int st_ = k_first + min((S), KT - 1);                                                    \
     const char* ws_ = Wp + st_ * 128;                                                              \
     const char* xs_ = Ap + st_ * 128;                                                              \
     unsigned char* dst_ = ring + ((S) % STAGES) * STAGE_BYTES;                                     \
@@ -133,6 +147,22 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g
   }
 #undef HMI_COPY_STAGE
   HMI_WAIT_VMCNT(0);                         // the trailing copies must have landed before the LDS is handed on
+  if (SPLIT) {
+    // partial sums of wavefronts 1.. go through their own (now idle) rings; wavefront 0 adds them in order
+    float* red = reinterpret_cast<float*>(ring);
+    if (wave != 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[r * 64 + lane] = acc[r];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int w = 1; w < KSPLIT; ++w) {
+      const float* part = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] += part[r * 64 + lane];
+    }
+  }
 
   // ---- epilogue: lane (row l32, half lh) holds columns n0 + 16 lh + r, r = 0..15
   if (l32 < rows) {
@@ -193,14 +223,22 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_skinny_kernel(GemmArgs g
 void launch_gemm_bf16_skinny(const GemmArgs& g, const Route& rt, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<false>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, KSPLIT * WAVE_LDS);
     attr_set = true;
   }
   const int row_split = g.n_rows > 32LL * g.n_mtiles ? 1 : 0;
   const long long n_items = (long long)g.n_mtiles * (g.n_out / SK) * (row_split ? 4 : 1);
   if (n_items <= 0) return;
-  hipLaunchKernelGGL(gemm_bf16_skinny_kernel, dim3((unsigned)((n_items + WAVES - 1) / WAVES)), dim3(64 * WAVES),
+  // few items, long k: one workgroup per item with k shared by its wavefronts
+  if (row_split && n_items <= kSplitMaxItems && g.k % (64 * KSPLIT) == 0 && g.k >= 64 * KSPLIT * 2) {
+    hipLaunchKernelGGL(gemm_bf16_skinny_kernel<true>, dim3((unsigned)n_items), dim3(64 * KSPLIT), KSPLIT * WAVE_LDS, s,
+                       g, rt, (int)n_items, row_split);
+    return;
+  }
+  hipLaunchKernelGGL(gemm_bf16_skinny_kernel<false>, dim3((unsigned)((n_items + WAVES - 1) / WAVES)), dim3(64 * WAVES),
                      LDS_BYTES, s, g, rt, (int)n_items, row_split);
 }
 

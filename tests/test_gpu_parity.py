@@ -294,15 +294,19 @@ def test_output_heads_ragged(hmi, dtype, d_model):
         pool.close()
 
 
-@pytest.mark.parametrize("block", [synth.BLOCK_DEC_PRELN, synth.BLOCK_DEC_ADAPTER])
-def test_decode_steps_with_kv_cache_match_full_causal_forward(hmi, block):
+@pytest.mark.parametrize("block,kw", [
+    (synth.BLOCK_DEC_PRELN, {}), (synth.BLOCK_DEC_ADAPTER, {}),
+    # 70 rows through shared matrices with k = 1024: the launch that shares an item's k between four wavefronts
+    (synth.BLOCK_DEC_ADAPTER, dict(d_model=256, d_ff=1024, n_heads=4, n_requests=70, n_tenants=9, hbm_slots=9, seq_max=40)),
+], ids=["own_layer", "shared_layer", "shared_layer_70_rows"])
+def test_decode_steps_with_kv_cache_match_full_causal_forward(hmi, block, kw):
     """Prefill ragged prompts of many tenants, then generate: every decode step's row must equal the
     last row of the oracle's full causal forward over the sequence so far (two layers, so the second
     layer's cache holds first-layer outputs).  Some requests stop early, so lines of different
     lengths and a shrinking batch are covered; sequence slots are a scattered subset of the lines."""
     from paper_2504_17449_amd import harness, HmiError, HMI_ERR_SHAPE, HMI_ERR_ARG
     from tests.oracle_side import weights_of
-    wl = small(block, "bf16", n_layers=2, n_tenants=6, hbm_slots=6, n_requests=14, seq_max=70)
+    wl = small(block, "bf16", **{**dict(n_layers=2, n_tenants=6, hbm_slots=6, n_requests=14, seq_max=70), **kw})
     ids, lens = synth.batch_ids_lens(wl)
     R, L, G = len(ids), wl.n_layers, 5
     full = [synth.hidden_states(wl, r, int(lens[r]) + G) for r in range(R)]
