@@ -38,3 +38,12 @@ def test_argument_errors_need_no_gpu():
     rc, h = pkg.hmi_pool_create(block=0, dtype=1, d_model=100, d_ff=64, max_tenants=1,
                                 max_requests=1, max_tokens=1)
     assert rc == pkg.HMI_ERR_ARG and "multiples" in pkg.hmi_last_error(None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other --gpus exits non-zero with a message that says so, before torch is imported."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
