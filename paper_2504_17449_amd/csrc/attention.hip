@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, Route rt) {
   const int n_keys = a.causal ? q_last + 1 : len;              // keys any query here can see
   const int wave_q_last = q0 + wave * 32 + 31;
   const bool wave_has_rows = q0 + wave * 32 < len;
-  const float scale = 0.125f;                                  // 1/sqrt(64)
+  constexpr float kExpScale = 0.125f * 1.4426950408889634f;    // log2(e) / sqrt(64)
 
   // A key block goes global -> registers -> LDS; the registers of the next block are loaded while this
   // one is multiplied.  K: 64 keys x 8 chunks of 16 bytes, two per thread, swizzled.  V^T: thread (key
@@ -121,29 +121,38 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a, Route rt) {
         s[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[tt], 0, 0, 0);
       }
     }
-    // ---- scale, mask, block max.  s[tt][i] is key k0 + tt*32 + 8*(i/4) + 4*lh + i%4, query q.
+    // ---- mask, block max, exponentials.  s[tt][i] is key k0 + tt*32 + 8*(i/4) + 4*lh + i%4, query q.
+    // The scores stay unscaled: exp((s - m) / 8) is one fma and one exp2 with c = log2(e) / 8.  Only a
+    // block that reaches past the request's end or past this wavefront's first query (causal) has
+    // keys to mask, which is the same for all lanes of the wavefront.
+    const bool need_mask = k0 + KB > len || (a.causal && k0 + KB - 1 > q0 + wave * 32);
+    if (need_mask) {
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = k0 + tt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+          const bool ok = key < len && (!a.causal || key <= q);
+          s[tt][i] = ok ? s[tt][i] : -INFINITY;
+        }
+    }
     float m_blk = -INFINITY;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = k0 + tt * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-        const bool ok = key < len && (!a.causal || key <= q);
-        const float v = ok ? s[tt][i] * scale : -INFINITY;
-        s[tt][i] = v;
-        m_blk = fmaxf(m_blk, v);
-      }
+      for (int i = 0; i < 16; ++i) m_blk = fmaxf(m_blk, s[tt][i]);
     m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32, 64));
     const float m_new = fmaxf(m_run, m_blk);
     // queries past the request end (or fully masked so far) keep m_new = -inf: use 0 there
     const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-    const float alpha = __expf(m_run - m_use);
+    const float mc = m_use * kExpScale;
+    const float alpha = __builtin_amdgcn_exp2f(fmaf(m_run, kExpScale, -mc));
     float psum = 0.0f;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float p = __expf(s[tt][i] - m_use);
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[tt][i], kExpScale, -mc));
         s[tt][i] = p;
         psum += p;
       }
