@@ -130,6 +130,54 @@ def test_hgpt_decode_steps_full_size_sampled():
         assert ok, (g, max_abs, rel)
 
 
+def test_shared_decoder_decode_steps_full_size_sampled():
+    """bench.py --workload hgpt_shared_adapter --decode as it runs (256 ragged prompts, d = 768, shared decoder layers
+    with tenant adapters; two layers, for which both bars hold): prefill, then two decode steps.  With 256 rows the
+    output projection and FFN2 of a decode step are the launches that share an item's k between four wavefronts.
+    By causality one oracle forward over prompt + 2 positions gives a sampled request's prefill rows and both
+    decode rows."""
+    from paper_2504_17449_amd import harness
+    from tests.oracle_side import weights_of
+    wl = synth.WORKLOADS["hgpt_shared_adapter"].scaled(n_layers=2)
+    ids, lens = synth.batch_ids_lens(wl)
+    R, G, L = len(ids), 2, wl.n_layers
+    full = [synth.hidden_states(wl, r, int(lens[r]) + G) for r in range(R)]
+    slots = np.arange(R, dtype=np.int32)[::-1].copy()
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl, sorted(set(ids.tolist())), workers=16)
+        pool.kv_create(R, int(lens.max()) + G)
+        x = harness.host_to_device(np.concatenate([full[r][:lens[r]] for r in range(R)]), "bf16")
+        y = torch.empty_like(x)
+        pool.prefill(0, L, x, y, ids, lens, slots)
+        outs = []
+        for g in range(G):
+            xn = harness.host_to_device(np.stack([full[r][lens[r] + g] for r in range(R)]), "bf16")
+            yn = torch.empty_like(xn)
+            pool.decode_step(0, L, xn, yn, ids, slots)
+            outs.append(yn)
+        torch.cuda.synchronize()
+        y_pre = harness.device_to_f64(y)
+        outs = [harness.device_to_f64(o) for o in outs]
+    finally:
+        pool.close()
+    sample = pick_sample(ids, lens, n_multi=2, n_single=3)
+    wof = [weights_of(wl, l) for l in range(L)]
+    tok = np.concatenate([[0], np.cumsum(lens)])
+    t1 = time.time()
+    for r in sample:
+        cur = full[r].astype(np.float64)
+        for l in range(L):
+            cur = O.block_forward(wl.block, cur, wof[l](int(ids[r])), wl.n_heads, wl.ln_eps)
+        n = int(lens[r])
+        max_abs, rel, ok = compare(y_pre[tok[r]:tok[r] + n], cur[:n], np.arange(n), "bf16")
+        assert ok, ("prefill", r, max_abs, rel)
+        for g in range(G):
+            max_abs, rel, ok = compare(outs[g][r:r + 1], cur[n + g:n + g + 1], np.arange(1), "bf16")
+            assert ok, ("decode", g, r, max_abs, rel)
+    print(f"  {len(sample)} sampled requests, prefill rows and {G} decode rows each, oracle {time.time() - t1:.1f}s", flush=True)
+
+
 # ------------------------------------------------------------------ host tier
 
 class LruModel:
