@@ -67,7 +67,8 @@ enum { HMI_BLOCK_FFN = 0, HMI_BLOCK_ENC_POSTLN = 1, HMI_BLOCK_DEC_PRELN = 2, HMI
 typedef struct {
   int32_t block;        /* HMI_BLOCK_*                                                    */
   int32_t dtype;        /* HMI_F32 | HMI_BF16: storage type of weights, x and y           */
-  int32_t d_model;      /* multiple of 64 (bf16) / 16 (f32)                               */
+  int32_t d_model;      /* multiple of 64 (bf16) / 16 (f32); max_tokens * max(d_model, d_ff)
+                           * element size must stay below 4 GiB (32-bit row offsets)      */
   int32_t d_ff;         /* FFN width, or adapter rank; multiple of 64 (bf16) / 16 (f32)   */
   int32_t n_heads;      /* attention blocks: d_model / n_heads must be 64; else 0         */
   int32_t n_layers;     /* per-tenant layers held per tenant (>= 1)                       */
@@ -189,7 +190,9 @@ int32_t hmi_pool_load_head(hmi_pool_t* pool, int32_t tenant_id, const void* w, c
  * HMI_ERR_ARG; a tenant of that batch without a head -> HMI_ERR_TENANT (nothing enqueued). */
 int32_t hmi_head_forward(hmi_pool_t* pool, const void* h, float* scores, int32_t* labels);
 
-/* Routing of the last forward call, for bit-exact checks of the tenant-segmented router:
+/* The grouping of the last forward call's requests by tenant (Sec. 6.3 batches the requests of
+ * different instances into one set of launches; this is the order they were grouped in), for
+ * bit-exact checks of the tenant-segmented router:
  * perm[R] (stable order of requests by tenant id), seg_tenant[G], seg_req_off[G+1],
  * seg_tok_off[G+1] (segment bounds in sorted requests / sorted tokens), *n_segments = G.
  * All HOST buffers sized for max_requests(+1); any may be NULL.  Waits for the router. */
@@ -202,7 +205,8 @@ int32_t hmi_get_route(hmi_pool_t* pool, int32_t* perm, int32_t* seg_tenant,
  * host_tier.  Best effort: stops silently when no evictable slot is left. */
 int32_t hmi_pool_prefetch(hmi_pool_t* pool, int32_t layer, const int32_t* tenant_ids, int32_t n);
 
-/* Counters since creation: hits / misses count distinct (tenant, layer) lookups made by
+/* Swapping statistics (Sec. 5.2: task parameters are brought to the GPU only when their instance
+ * is requested).  Counters since creation: hits / misses count distinct (tenant, layer) lookups made by
  * forward calls; bytes_h2d counts swap-in traffic.  Any pointer may be NULL. */
 int32_t hmi_pool_stats(hmi_pool_t* pool, int64_t* hits, int64_t* misses, int64_t* bytes_h2d,
                        int64_t* evictions);
@@ -223,7 +227,9 @@ int64_t hmi_pool_image_bytes(const hmi_pool_t* pool);
  * pool is NULL).  Valid until the next call on the pool. */
 const char* hmi_last_error(const hmi_pool_t* pool);
 
-/* Waits for both streams, frees everything the library owns.  NULL is fine. */
+/* Deletes every instance of the pool (Sec. 4.1, "delete hPLM", for all of them at once): waits
+ * for both streams, then frees the HBM slots, pinned host images, workspaces, the copy stream and
+ * the events.  The handle is invalid afterwards.  NULL is fine. */
 int32_t hmi_pool_destroy(hmi_pool_t* pool);
 
 #ifdef __cplusplus

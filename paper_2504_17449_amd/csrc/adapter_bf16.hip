@@ -292,18 +292,8 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
 template <int NV>
 void launch_nv(const AdapterArgs& a, const Route& rt, hipStream_t s) {
   using S = Shape<NV>;
-  static bool attr_set = false;
-  static int n_cu = 0;
   auto kern = adapter_bf16_kernel<NV>;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
-    attr_set = true;
-  }
-  if (n_cu == 0) {
-    int dev = 0;
-    (void)hipGetDevice(&dev);
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) n_cu = 256;
-  }
+  const int n_cu = rt.n_cu >= 1 ? rt.n_cu : 256;
   const long long U = (long long)a.n_tiles128 * 4;
   if (U <= 0) return;
   long long grid = U < n_cu ? U : n_cu;                               // one workgroup per compute unit ...
@@ -312,7 +302,15 @@ void launch_nv(const AdapterArgs& a, const Route& rt, hipStream_t s) {
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTH), S::LDS, s, a, rt);
 }
 
+template <int NV>
+void allow_lds() {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(adapter_bf16_kernel<NV>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            Shape<NV>::LDS);
+}
+
 }  // namespace
+
+void init_adapter_bf16_kernels() { allow_lds<1>(); allow_lds<2>(); allow_lds<3>(); }
 
 // Operand order: 1 KB blocks, one per (32-row block, 16-wide k-step), k-steps innermost.
 // Lane l of a block holds the 8 elements [16 s + 8 (l / 32), +8) of the block's row

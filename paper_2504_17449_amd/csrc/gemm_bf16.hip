@@ -424,13 +424,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(GemmArgs g, Rou
 }
 
 template <typename Kern>
-void launch_kernel(Kern kern, bool& attr_set, size_t lds, int bn, int nth, const GemmArgs& g, const Route& rt,
-                   hipStream_t s) {
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_set = true;
-  }
+void launch_kernel(Kern kern, size_t lds, int bn, int nth, const GemmArgs& g, const Route& rt, hipStream_t s) {
   const int nt_n = (g.n_out + bn - 1) / bn;
   const long long total = (long long)g.n_mtiles * nt_n;
   if (total <= 0) return;
@@ -439,22 +433,37 @@ void launch_kernel(Kern kern, bool& attr_set, size_t lds, int bn, int nth, const
 }
 
 template <int BM, int BN, int WM, int WN>
-void launch_staged(const GemmArgs& g, const Route& rt, hipStream_t s) {
-  static bool attr_set = false;
+constexpr size_t staged_lds() {
   constexpr size_t stages = (size_t)2 * (BM + BN) * BK * 2, patches = (size_t)WM * WN * epi_patch_bytes<BN / WN>();
-  launch_kernel(gemm_bf16_kernel<BM, BN, WM, WN>, attr_set, (stages > patches ? stages : patches) + BM * sizeof(int),
-                BN, 64 * WM * WN, g, rt, s);
+  return (stages > patches ? stages : patches) + BM * sizeof(int);
+}
+template <int BM, int BN, int WM, int WN, int STAGES>
+constexpr size_t dma_lds() {
+  constexpr size_t stages = (size_t)STAGES * (BM + BN) * 32 * 2, patches = (size_t)WM * WN * epi_patch_bytes<BN / WN>();
+  return (stages > patches ? stages : patches) + BM * sizeof(int);
+}
+
+template <int BM, int BN, int WM, int WN>
+void launch_staged(const GemmArgs& g, const Route& rt, hipStream_t s) {
+  launch_kernel(gemm_bf16_kernel<BM, BN, WM, WN>, staged_lds<BM, BN, WM, WN>(), BN, 64 * WM * WN, g, rt, s);
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES>
 void launch_dma(const GemmArgs& g, const Route& rt, hipStream_t s) {
-  static bool attr_set = false;
-  constexpr size_t stages = (size_t)STAGES * (BM + BN) * 32 * 2, patches = (size_t)WM * WN * epi_patch_bytes<BN / WN>();
-  launch_kernel(gemm_bf16_dma_kernel<BM, BN, WM, WN, STAGES>, attr_set,
-                (stages > patches ? stages : patches) + BM * sizeof(int), BN, 64 * WM * WN, g, rt, s);
+  launch_kernel(gemm_bf16_dma_kernel<BM, BN, WM, WN, STAGES>, dma_lds<BM, BN, WM, WN, STAGES>(), BN, 64 * WM * WN, g, rt, s);
 }
 
 }  // namespace
+
+// the three general-tile kernels launch_gemm_bf16 can pick
+void init_gemm_bf16_kernels() {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_dma_kernel<256, 256, 4, 2, 4>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds<256, 256, 4, 2, 4>());
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<256, 128, 4, 2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)staged_lds<256, 128, 4, 2>());
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel<256, 64, 8, 1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)staged_lds<256, 64, 8, 1>());
+}
 
 void launch_gemm_bf16(const GemmArgs& g0, const Route& rt, hipStream_t s) {
   GemmArgs g = g0;

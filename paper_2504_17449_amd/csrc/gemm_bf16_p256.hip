@@ -484,18 +484,8 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
 
 template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
 void launch_one(const GemmArgs& g, const Route& rt, hipStream_t s) {
-  static bool attr_set = false;
-  static int n_cu = 0;
   auto kern = gemm_bf16_p256_kernel<EPI, OUT_F32, RESID_F32, HAS_C2>;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    attr_set = true;
-  }
-  if (n_cu == 0) {
-    int dev = 0;
-    (void)hipGetDevice(&dev);
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < kXcds) n_cu = 256;
-  }
+  const int n_cu = rt.n_cu >= kXcds ? rt.n_cu : 256;
   const int nt_n = g.n_out / BN;
   const long long total = (long long)g.n_mtiles * nt_n;
   if (total <= 0) return;
@@ -504,8 +494,23 @@ void launch_one(const GemmArgs& g, const Route& rt, hipStream_t s) {
   hipLaunchKernelGGL(kern, dim3(local * kXcds), dim3(NTH), LDS_BYTES, s, g, rt, (int)total, per_xcd);
 }
 
+template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
+void allow_lds() {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_p256_kernel<EPI, OUT_F32, RESID_F32, HAS_C2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+}
+
 }  // namespace
 
+// every instantiation launch_gemm_bf16_p256 can pick
+void init_gemm_bf16_p256_kernels() {
+  allow_lds<EPI_BIAS, false, false, true>();   allow_lds<EPI_BIAS, false, false, false>();
+  allow_lds<EPI_BIAS_GELU, false, false, false>();
+  allow_lds<EPI_BIAS_RELU, false, false, false>();
+  allow_lds<EPI_BIAS_RESID, true, true, true>();   allow_lds<EPI_BIAS_RESID, true, true, false>();
+  allow_lds<EPI_BIAS_RESID, true, false, true>();  allow_lds<EPI_BIAS_RESID, true, false, false>();
+  allow_lds<EPI_BIAS_RESID, false, true, false>(); allow_lds<EPI_BIAS_RESID, false, false, false>();
+}
 
 // Preconditions (checked by the caller): n_out % 256 == 0, k % 64 == 0, k >= 192,
 // which_tiles names a list of 256-row m-tiles, all operands 16-byte aligned,

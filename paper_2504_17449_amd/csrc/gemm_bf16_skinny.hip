@@ -218,17 +218,16 @@ __global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinn
 
 }  // namespace
 
+void init_gemm_bf16_skinny_kernels() {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, KSPLIT * WAVE_LDS);
+}
+
 // Preconditions (checked by the caller): k % 64 == 0, n_out % 32 == 0, which_tiles names the list of
 // 128-row m-tiles and n_mtiles its length, all operands 16-byte aligned (lda, ldc, ldr multiples of 8).
 void launch_gemm_bf16_skinny(const GemmArgs& g, const Route& rt, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, KSPLIT * WAVE_LDS);
-    attr_set = true;
-  }
   const int row_split = g.n_rows > 32LL * g.n_mtiles ? 1 : 0;
   const long long n_items = (long long)g.n_mtiles * (g.n_out / SK) * (row_split ? 4 : 1);
   if (n_items <= 0) return;

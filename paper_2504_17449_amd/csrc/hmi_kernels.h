@@ -44,10 +44,18 @@ struct Route {
   // shorter), which all name slot 0; its tile lists and row map do not depend on the batch.
   int32_t* dense_seg_tok_off;   // [ceil(N / kDenseSegRows) + 1]
   int32_t* dense_n_segments;    // [1]
+  int32_t n_cu;                 // compute units of the pool's device (host side: sizes the persistent launches)
 };
 constexpr int kGemmSchedInts = 16 + 1024;
 
 void launch_router(const Route& rt, int R, hipStream_t s);
+
+// Per-device set-up of the kernels that need more than the default dynamic LDS: pool creation
+// calls these once per device, with that device current, before any launch on it.
+void init_gemm_bf16_kernels();
+void init_gemm_bf16_p256_kernels();
+void init_gemm_bf16_skinny_kernels();
+void init_adapter_bf16_kernels();
 
 enum Epilogue : int {
   EPI_BIAS = 0,        // C = acc + b                      -> storage dtype

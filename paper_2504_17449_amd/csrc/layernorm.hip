@@ -33,13 +33,14 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a, Route rt) {
   }
   const size_t slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
   const size_t row = (size_t)rt.row_src[srow];
-  const int d = a.d, per = d >> 6;
+  const int d = a.d, per = (d + 63) >> 6;   // columns lane, lane + 64, ... below d
 
   float v[kMaxPerLane];
   float s = 0.0f;
 #pragma unroll
   for (int i = 0; i < kMaxPerLane; ++i) {
-    if (i < per) {
+    v[i] = 0.0f;
+    if (i < per && lane + 64 * i < d) {
       const size_t idx = row * d + lane + 64 * i;
       if (a.in_f32) v[i] = reinterpret_cast<const float*>(a.in)[idx];
       else v[i] = BF16 ? bf2f(reinterpret_cast<const uint16_t*>(a.in)[idx])
@@ -54,12 +55,12 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a, Route rt) {
   float q = 0.0f;
 #pragma unroll
   for (int i = 0; i < kMaxPerLane; ++i)
-    if (i < per) { const float c = v[i] - mean; q += c * c; }
+    if (i < per && lane + 64 * i < d) { const float c = v[i] - mean; q += c * c; }
   const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + a.eps);
 
 #pragma unroll
   for (int i = 0; i < kMaxPerLane; ++i) {
-    if (i < per) {
+    if (i < per && lane + 64 * i < d) {
       const int col = lane + 64 * i;
       float gg, bb;
       if (BF16) {

@@ -13,6 +13,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -57,6 +58,31 @@ struct EventRing {
 
 struct TensorLoc { size_t off, bytes; };
 
+}  // namespace
+
+namespace {
+// Per-device set-up, once per device and process: the kernels' dynamic-LDS limits and the number
+// of compute units.  Guarded, so that pools may be created from several threads.
+constexpr int kMaxDevices = 64;
+std::mutex g_device_mu;
+int g_device_cus[kMaxDevices] = {};        // 0 = this device has not been set up yet
+
+// Call with `device` current.  Returns its compute-unit count, or 0 on failure.
+int device_setup(int device) {
+  if (device < 0 || device >= kMaxDevices) return 0;
+  std::lock_guard<std::mutex> lock(g_device_mu);
+  if (g_device_cus[device] == 0) {
+    int n_cu = 0;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n_cu < 1) return 0;
+    init_gemm_bf16_kernels();
+    init_gemm_bf16_p256_kernels();
+    init_gemm_bf16_skinny_kernels();
+    init_adapter_bf16_kernels();
+    if (hipGetLastError() != hipSuccess) return 0;
+    g_device_cus[device] = n_cu;
+  }
+  return g_device_cus[device];
+}
 }  // namespace
 
 struct hmi_pool {
@@ -133,10 +159,11 @@ struct hmi_pool {
   float *w_z = nullptr, *w_x1 = nullptr, *w_y32 = nullptr;
   char* w_yst = nullptr;       // inter-layer activations of a multi-layer call
 
-  // host scratch
+  // host scratch, sized at creation: the forward calls allocate nothing
   std::vector<uint32_t> mark;       // [tenant] epoch when last seen in a batch
   std::vector<int32_t> tok_count;   // [tenant]
-  std::vector<int32_t> distinct;
+  std::vector<int32_t> distinct;    // capacity max_requests
+  std::vector<int32_t> ones;        // [max_requests] the sequence lengths of a decode step
   uint32_t epoch = 0;
 
   int64_t hits = 0, misses = 0, bytes_h2d = 0, evictions = 0;
@@ -352,6 +379,10 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
     return fail(nullptr, HMI_ERR_ARG, "without host_tier every tenant needs a slot: hbm_slots must equal max_tenants");
   if (!(c.ln_eps >= 0.0f)) return fail(nullptr, HMI_ERR_ARG, "ln_eps must be >= 0");
   if (c.max_classes < 0 || c.max_classes > 64) return fail(nullptr, HMI_ERR_ARG, "max_classes must be in [0, 64]");
+  // the kernels address activation rows with 32-bit byte offsets
+  if ((uint64_t)c.max_tokens * (uint64_t)std::max(c.d_model, c.d_ff) * (c.dtype == HMI_BF16 ? 2u : 4u) >= (1ull << 32))
+    return fail(nullptr, HMI_ERR_ARG, "max_tokens * max(d_model, d_ff) * element size must stay below 4 GiB");
+  if (c.device < 0 || c.device >= kMaxDevices) return fail(nullptr, HMI_ERR_ARG, "device %d outside [0,%d)", c.device, kMaxDevices);
 
   hmi_pool* p = new (std::nothrow) hmi_pool();
   if (!p) return fail(nullptr, HMI_ERR_OOM, "host allocation failed");
@@ -394,6 +425,11 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   } while (0)
 
   CREATE_TRY(hipSetDevice(c.device));
+  const int n_cu = device_setup(c.device);
+  if (n_cu == 0) {
+    free_all(p);
+    return fail(nullptr, HMI_ERR_DEVICE, "kernel set-up on device %d failed", c.device);
+  }
   p->compute = reinterpret_cast<hipStream_t>(c.compute_stream);
   CREATE_TRY(hipStreamCreateWithFlags(&p->copy, hipStreamNonBlocking));
   if (!p->fwd_done.init() || !p->copy_done.init()) {
@@ -423,6 +459,9 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   if (c.host_tier) p->host_img.assign(c.max_tenants, nullptr);
   p->mark.assign(c.max_tenants, 0);
   p->tok_count.assign(c.max_tenants, 0);
+  p->distinct.reserve(c.max_requests);
+  p->last_distinct.reserve(c.max_requests);
+  p->ones.assign(c.max_requests, 1);
 
   if (!c.host_tier) {
     for (int i = 0; i < 2; ++i) {
@@ -470,6 +509,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   rt.gemm_sched = take(kGemmSchedInts);
   rt.tile_m[0] = p->tile_m[0]; rt.tile_m[1] = p->tile_m[1];
   rt.key_bits = bits_for(c.max_tenants);
+  rt.n_cu = n_cu;
   if (dense) {
     // Route for the shared parameters: identity row map, pseudo-segments of kDenseSegRows rows
     // that all name slot 0 (the GEMMs get a slot stride of 0), tiles in row order.  Only the
@@ -734,13 +774,12 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
                             const int32_t* seq_slots) {
   if (!p) return HMI_ERR_ARG;
   if (R == 0) return HMI_OK;
-  std::vector<int32_t> ones;
-  if (kv == KV_DECODE && R > 0) { ones.assign(R, 1); seq_lens = ones.data(); }
+  if (kv == KV_DECODE && R > 0 && R <= p->cfg.max_requests) seq_lens = p->ones.data();
+  if (R > p->cfg.max_requests) return fail(p, HMI_ERR_SHAPE, "%d requests > max_requests %d", R, p->cfg.max_requests);
   if (R < 0 || !x || !y || !tenant_ids || !seq_lens) return fail(p, HMI_ERR_ARG, "null pointer or negative request count");
   if (x == y) return fail(p, HMI_ERR_ARG, "x and y must be different buffers");
   if (layer_begin < 0 || layer_end > p->cfg.n_layers || layer_begin >= layer_end)
     return fail(p, HMI_ERR_ARG, "layers [%d,%d) outside [0,%d)", layer_begin, layer_end, p->cfg.n_layers);
-  if (R > p->cfg.max_requests) return fail(p, HMI_ERR_SHAPE, "%d requests > max_requests %d", R, p->cfg.max_requests);
   const hmi_pool_config_t& c = p->cfg;
   const int L = c.n_layers;
   if (!p->stl.empty())
@@ -815,6 +854,15 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
     *need_out = need;
     return HMI_OK;
   };
+  // Records the end of the kernels enqueued so far and notes it as the last reader of every slot
+  // this batch holds (a swap-in into one of them waits for that event).
+  auto mark_slots_read = [&]() {
+    const uint64_t seq = p->fwd_done.record(p->compute);
+    for (int t : p->distinct) {
+      const int sl = p->slot_of_tenant[t];
+      if (sl >= 0) p->slot_fwd[sl] = seq;
+    }
+  };
   uint64_t need_copy = 0;
   {
     int32_t rc = make_resident(layer_begin, true, &need_copy);
@@ -846,7 +894,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
   { ProfSpan ps(p, HMI_KERNEL_ROUTER); launch_router(rt, R, s); }
   HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
   p->last_R = R;
-  p->last_distinct = p->distinct;
+  p->last_distinct.assign(p->distinct.begin(), p->distinct.end());   // within the reserved capacity
   p->last_n_mtiles[0] = n_mtiles[0]; p->last_n_mtiles[1] = n_mtiles[1];
   p->last_N = (int)N;
 
@@ -871,7 +919,12 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
     uint64_t need_next = 0;
     if (!last) {
       int32_t rc = make_resident(layer + 1, true, &need_next);
-      if (rc != HMI_OK) return rc;
+      if (rc != HMI_OK) {
+        // earlier layers of this call may already be enqueued and reading their slots:
+        // later evictions have to wait for them like for a completed call
+        if (layer > layer_begin) mark_slots_read();
+        return rc;
+      }
     }
 
     const size_t lay = (size_t)layer * p->image_bytes;
@@ -1033,9 +1086,8 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
     in_res_f32 = true;
     need_copy = need_next;
   }
+  mark_slots_read();
   HIP_TRY(p, hipGetLastError());
-  const uint64_t seq = p->fwd_done.record(s);
-  for (int t : p->distinct) p->slot_fwd[p->slot_of_tenant[t]] = seq;
   if (kv == KV_PREFILL) for (int r = 0; r < R; ++r) p->kv_len[seq_slots[r]] = seq_lens[r];
   if (kv == KV_DECODE) for (int r = 0; r < R; ++r) p->kv_len[seq_slots[r]] += 1;
   return HMI_OK;

@@ -73,6 +73,17 @@ def test_small_fp32_blocks_ragged(hmi, block):
     run_case(hmi, small(block, "f32", d_model=64, d_ff=128, n_heads=4, seq_max=90))
 
 
+@pytest.mark.parametrize("block,kw", [
+    (synth.BLOCK_FFN, dict(d_model=80, d_ff=48)),
+    (synth.BLOCK_FFN, dict(d_model=48, d_ff=144)),
+    (synth.BLOCK_ENC_POSTLN, dict(d_model=80, d_ff=96, n_heads=5)),
+    (synth.BLOCK_DEC_PRELN, dict(d_model=144, d_ff=80, n_heads=3))])
+def test_fp32_widths_that_are_not_multiples_of_64(hmi, block, kw):
+    """fp32 pools take any width that is a multiple of 16: LayerNorm, GEMM and attention must cover the
+    columns beyond the last full group of 64 (d = 80, 144) and widths below 64 (d = 48)."""
+    run_case(hmi, small(block, "f32", seq_max=60, **kw))
+
+
 @pytest.mark.parametrize("block", [synth.BLOCK_FFN, synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN,
                                    synth.BLOCK_ADAPTER, synth.BLOCK_ENC_ADAPTER, synth.BLOCK_DEC_ADAPTER])
 def test_small_bf16_blocks_ragged(hmi, block):
@@ -501,13 +512,10 @@ def test_seeded_random_small_shapes(hmi, seed):
     run_case(hmi, small(block, "bf16", **kw), slack=7 * (seed % 2))    # odd seeds: a pool larger than the batch
 
 
-def test_bert_ffn_full_size_sampled(hmi):
-    wl = synth.WORKLOADS["bert_ffn"]
-    ids, _ = synth.batch_ids_lens(wl)
-    # first and last request of several segments, in arrival order
-    order = np.argsort(ids, kind="stable")
-    sample = sorted(set(order[::9].tolist() + [0, len(ids) - 1]))
-    run_case(hmi, wl, sample=sample, tenants="all")
+def test_bert_ffn_full_size_every_request(hmi):
+    """The benchmarked configuration (64 tenants, 256 requests of 128 tokens, d = 768, f = 3072) as bench.py
+    runs it, all 32 768 rows against the oracle."""
+    run_case(hmi, synth.WORKLOADS["bert_ffn"], tenants="all")
 
 
 def test_single_request_and_single_tenant(hmi):
