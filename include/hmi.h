@@ -125,6 +125,22 @@ int32_t hmi_layer_forward(hmi_pool_t* pool, int32_t layer, const void* x, void* 
                           const int32_t* tenant_ids, const int32_t* seq_lens,
                           int32_t n_requests);
 
+/* hmi_layer_forward for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same result, but the routing arrays
+ * the kernels work from (request order, segment offsets, row map, tile lists) live in a static
+ * device array of the library (0.17 MB per GPU, held until the process ends) instead of the pool's
+ * own allocation, and the call itself allocates and frees nothing, on the device or the host.
+ * Limits: a bf16 ADAPTER pool without host_tier whose forward is one kernel (rank d_ff = 64,
+ * d_model 256 / 512 / 768, n_layers = 1), else HMI_ERR_ARG; n_requests <= 256 and at most 32 768
+ * tokens (and the pool's own bounds), else HMI_ERR_SHAPE.  Other arguments, errors (y untouched)
+ * and asynchrony as hmi_layer_forward.  All pools on one GPU share that GPU's array: calls that
+ * may overlap in time on one GPU (different streams) race; calls ordered on one stream do not.
+ * Each call rewrites every entry it reads, so nothing carries over from the call before.
+ * hmi_get_route and hmi_head_forward keep referring to the last call that routed inside the pool. */
+int32_t hmi_layer_forward_static(hmi_pool_t* pool, int32_t layer, const void* x, void* y,
+                                 const int32_t* tenant_ids, const int32_t* seq_lens,
+                                 int32_t n_requests);
+
 /* Several consecutive layers [layer_begin, layer_end) of every request's tenant in one call
  * (the paper's hPLM runs a stack of task-adapted higher layers per request, Sec. 3.3.2, and
  * prefetches layer l+1's task parameters while layer l computes, Sec. 6.2).  Same arguments,

@@ -22,7 +22,7 @@ HMI_F32, HMI_BF16 = 0, 1
 HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER, HMI_BLOCK_DEC_ADAPTER = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward",
-           "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_plot_aggregate", "hmi_layer_forward", "hmi_stack_forward",
+           "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_plot_aggregate", "hmi_layer_forward", "hmi_layer_forward_static", "hmi_stack_forward",
            "hmi_get_route",
            "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
            "hmi_pool_destroy"]
@@ -69,6 +69,8 @@ def _load() -> C.CDLL:
     lib.hmi_decode_step.restype = i32
     lib.hmi_layer_forward.argtypes = [vp, i32, vp, vp, pi32, pi32, i32]
     lib.hmi_layer_forward.restype = i32
+    lib.hmi_layer_forward_static.argtypes = [vp, i32, vp, vp, pi32, pi32, i32]
+    lib.hmi_layer_forward_static.restype = i32
     lib.hmi_stack_forward.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
     lib.hmi_stack_forward.restype = i32
     lib.hmi_get_route.argtypes = [vp, pi32, pi32, pi32, pi32, pi32]
@@ -181,6 +183,14 @@ def hmi_layer_forward(pool: int, layer: int, x_ptr: int, y_ptr: int, tenant_ids,
     return lib.hmi_layer_forward(pool, layer, x_ptr, y_ptr, _p32(ids), _p32(lens), ids.shape[0])
 
 
+def hmi_layer_forward_static(pool: int, layer: int, x_ptr: int, y_ptr: int, tenant_ids, seq_lens) -> int:
+    """hmi_layer_forward through the library's static routing arrays (allocates nothing)."""
+    ids, lens = _i32(tenant_ids), _i32(seq_lens)
+    if ids.shape != lens.shape or ids.ndim != 1:
+        raise ValueError("tenant_ids and seq_lens must be 1-D and of equal length")
+    return lib.hmi_layer_forward_static(pool, layer, x_ptr, y_ptr, _p32(ids), _p32(lens), ids.shape[0])
+
+
 def hmi_stack_forward(pool: int, layer_begin: int, layer_end: int, x_ptr: int, y_ptr: int,
                       tenant_ids, seq_lens) -> int:
     ids, lens = _i32(tenant_ids), _i32(seq_lens)
@@ -281,6 +291,9 @@ class Pool:
     def forward(self, layer: int, x, y, tenant_ids, seq_lens) -> None:
         """x, y: torch tensors on the pool's device ([N, d], pool dtype, contiguous)."""
         self._check(hmi_layer_forward(self.h, layer, x.data_ptr(), y.data_ptr(), tenant_ids, seq_lens))
+
+    def forward_static(self, layer: int, x, y, tenant_ids, seq_lens) -> None:
+        self._check(hmi_layer_forward_static(self.h, layer, x.data_ptr(), y.data_ptr(), tenant_ids, seq_lens))
 
     def stack_forward(self, layer_begin: int, layer_end: int, x, y, tenant_ids, seq_lens) -> None:
         self._check(hmi_stack_forward(self.h, layer_begin, layer_end, x.data_ptr(), y.data_ptr(),

@@ -28,6 +28,18 @@ constexpr int kArenaImages = 32;  // pinned host images per hipHostMalloc call
 
 char g_create_error[256] = "";
 
+// Limits of hmi_layer_forward_static and the layout of its routing arrays inside `scratch`.
+constexpr int kStaticMaxRequests = 256;
+constexpr int kStaticMaxTokens = 32768;
+constexpr size_t kStaticTiles0 = kStaticMaxTokens / kBf16TileM0 + kStaticMaxRequests + 1;
+constexpr size_t kStaticTiles1 = kStaticMaxTokens / kBf16TileM1 + kStaticMaxRequests + 1;
+constexpr size_t kStaticIndexInts =              // nine per-request arrays, three of them one entry longer; three counters
+    (size_t)kStaticMaxRequests * 9 + 3 + 3;
+constexpr size_t kStaticScratchInts =
+    kStaticIndexInts
+    + kStaticMaxTokens                            // row_src
+    + 2 * (kStaticTiles0 + kStaticTiles1);        // the two m-tile lists
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Events for work enqueued in order on one stream, addressed by a growing sequence
@@ -60,12 +72,18 @@ struct TensorLoc { size_t off, bytes; };
 
 }  // namespace
 
+// Routing arrays of hmi_layer_forward_static (0.17 MB per GPU, held until the process ends).  In host
+// code this name only stands for the symbol: device_setup() asks each device for the address of its
+// own copy and every use below goes through that address.
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
+
 namespace {
 // Per-device set-up, once per device and process: the kernels' dynamic-LDS limits and the number
 // of compute units.  Guarded, so that pools may be created from several threads.
 constexpr int kMaxDevices = 64;
 std::mutex g_device_mu;
 int g_device_cus[kMaxDevices] = {};        // 0 = this device has not been set up yet
+int32_t* g_scratch_ptr[kMaxDevices] = {};  // each device's own copy of `scratch`
 
 // Call with `device` current.  Returns its compute-unit count, or 0 on failure.
 int device_setup(int device) {
@@ -79,6 +97,9 @@ int device_setup(int device) {
     init_gemm_bf16_skinny_kernels();
     init_adapter_bf16_kernels();
     if (hipGetLastError() != hipSuccess) return 0;
+    int32_t* ptr = nullptr;
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return 0;
+    g_scratch_ptr[device] = ptr;
     g_device_cus[device] = n_cu;
   }
   return g_device_cus[device];
@@ -1127,6 +1148,92 @@ int32_t hmi_decode_step(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, c
 int32_t hmi_layer_forward(hmi_pool_t* p, int32_t layer, const void* x, void* y,
                           const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
   return hmi_stack_forward(p, layer, layer + 1, x, y, tenant_ids, seq_lens, R);
+}
+
+int32_t hmi_layer_forward_static(hmi_pool_t* p, int32_t layer, const void* x, void* y,
+                                 const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
+  if (!p) return HMI_ERR_ARG;
+  if (R == 0) return HMI_OK;
+  const hmi_pool_config_t& c = p->cfg;
+  if (c.block != HMI_BLOCK_ADAPTER || !p->adapter_fused || c.host_tier)
+    return fail(p, HMI_ERR_ARG, "hmi_layer_forward_static needs a bf16 ADAPTER pool without host tier that runs as one kernel "
+                                "(rank 64, d_model 256 / 512 / 768, one layer)");
+  if (R < 0 || !x || !y || !tenant_ids || !seq_lens) return fail(p, HMI_ERR_ARG, "null pointer or negative request count");
+  if (x == y) return fail(p, HMI_ERR_ARG, "x and y must be different buffers");
+  if (layer != 0) return fail(p, HMI_ERR_ARG, "layer %d outside [0,1)", layer);
+  if (R > c.max_requests || R > kStaticMaxRequests)
+    return fail(p, HMI_ERR_SHAPE, "%d requests > limit %d", R, std::min(c.max_requests, kStaticMaxRequests));
+  if (++p->epoch == 0) { std::fill(p->mark.begin(), p->mark.end(), 0u); p->epoch = 1; }
+  p->distinct.clear();
+  const int64_t max_tokens = std::min<int64_t>(c.max_tokens, kStaticMaxTokens);
+  int64_t N = 0;
+  for (int r = 0; r < R; ++r) {
+    const int t = tenant_ids[r], len = seq_lens[r];
+    if (len <= 0) return fail(p, HMI_ERR_SHAPE, "seq_lens[%d] = %d", r, len);
+    if (t < 0 || t >= c.max_tenants) return fail(p, HMI_ERR_TENANT, "tenant_ids[%d] = %d outside [0,%d)", r, t, c.max_tenants);
+    if (!p->loaded[t] || p->slot_of_tenant[t] < 0) return fail(p, HMI_ERR_TENANT, "tenant %d was never loaded", t);
+    if (p->mark[t] != p->epoch) { p->mark[t] = p->epoch; p->tok_count[t] = 0; p->distinct.push_back(t); }
+    p->tok_count[t] += len;
+    N += len;
+    if (N > max_tokens) return fail(p, HMI_ERR_SHAPE, "batch has more than %d tokens", (int)max_tokens);
+  }
+  HIP_TRY(p, hipSetDevice(c.device));
+  int32_t* const base = g_scratch_ptr[c.device];
+  if (!base) return fail(p, HMI_ERR_DEVICE, "the static routing arrays of device %d were never resolved", c.device);
+  int n_tiles128 = 0;
+  uint64_t need_copy = 0;
+  for (int t : p->distinct) {
+    n_tiles128 += (p->tok_count[t] + kBf16TileM1 - 1) / kBf16TileM1;
+    need_copy = std::max(need_copy, p->slot_copy[p->slot_of_tenant[t]]);
+  }
+  hipStream_t s = p->compute;
+  if (need_copy > p->compute_waited_copy) {   // weights loaded just before this call
+    HIP_TRY(p, hipStreamWaitEvent(s, p->copy_done.at_least(need_copy), 0));
+    p->compute_waited_copy = need_copy;
+  }
+  // index arrays: through one of the pool's pinned buffers, read in place by the router
+  const int bi = p->idx_i;
+  p->idx_i = (p->idx_i + 1) & 3;
+  HIP_TRY(p, hipEventSynchronize(p->idx_ev[bi]));
+  int32_t* h = p->h_idx[bi];
+  const int Rm = c.max_requests;
+  for (int r = 0; r < R; ++r) {
+    h[r] = tenant_ids[r];
+    h[Rm + r] = seq_lens[r];
+    h[2 * Rm + r] = p->slot_of_tenant[tenant_ids[r]];
+  }
+  // routing arrays: fixed places inside this device's copy of `scratch`; the router writes every
+  // entry the adapter kernel reads, so nothing has to be cleared between calls
+  int32_t* q = base;
+  auto take = [&](size_t n) { int32_t* r = q; q += n; return r; };
+  constexpr size_t SR = kStaticMaxRequests;
+  Route rt{};
+  rt.tenant_ids = h; rt.seq_lens = h + Rm; rt.req_slot = h + 2 * Rm;
+  rt.req_tenant = take(SR); rt.kv_slot = take(SR); rt.kv_pos = take(SR);
+  rt.perm = take(SR); rt.tok_off = take(SR + 1);
+  rt.seg_tenant = take(SR); rt.seg_slot = take(SR);
+  rt.seg_req_off = take(SR + 1); rt.seg_tok_off = take(SR + 1);
+  rt.n_segments = take(1); rt.n_tiles[0] = take(1); rt.n_tiles[1] = take(1);
+  if ((size_t)(q - base) != kStaticIndexInts) return fail(p, HMI_ERR_DEVICE, "layout of the static routing arrays is inconsistent");
+  rt.row_src = take(kStaticMaxTokens);
+  rt.tile_seg[0] = take(kStaticTiles0); rt.tile_row0[0] = take(kStaticTiles0);
+  rt.tile_seg[1] = take(kStaticTiles1); rt.tile_row0[1] = take(kStaticTiles1);
+  if ((size_t)(q - base) != kStaticScratchInts) return fail(p, HMI_ERR_DEVICE, "layout of the static routing arrays is inconsistent");
+  rt.tile_m[0] = kBf16TileM0; rt.tile_m[1] = kBf16TileM1;
+  rt.key_bits = p->rt.key_bits;
+  rt.n_cu = p->rt.n_cu;
+  launch_router(rt, R, s);
+  HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
+  AdapterArgs a{};
+  a.X = x; a.Y = y; a.pool = p->d_pool; a.slot_stride = p->slot_stride;
+  a.wd_off = p->tl[T_W1].off; a.bd_off = p->tl[T_B1].off;
+  a.wu_off = p->tl[T_W2].off; a.bu_off = p->tl[T_B2].off;
+  a.d = c.d_model; a.which_tiles = 1; a.n_tiles128 = n_tiles128;
+  launch_adapter_bf16(a, rt, s);
+  const uint64_t seq = p->fwd_done.record(s);
+  for (int t : p->distinct) p->slot_fwd[p->slot_of_tenant[t]] = seq;
+  HIP_TRY(p, hipGetLastError());
+  return HMI_OK;
 }
 
 int32_t hmi_get_route(hmi_pool_t* p, int32_t* perm, int32_t* seg_tenant, int32_t* seg_req_off,
