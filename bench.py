@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=256, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--tenants", type=int, default=0, help="override the workload's tenant count (host-tier runs at reduced size)")
     ap.add_argument("--slots", type=int, default=0, help="override the number of HBM slots")
+    ap.add_argument("--images", type=int, default=-1,
+                    help="host-tier workloads: distinct weight sets in pinned memory; tenant t owns set t mod IMAGES "
+                         "(default: 500 for hbert_10k, whose 10 000 images of 14 MB exceed what can be pinned; 0 = one per tenant)")
     ap.add_argument("--decode", type=int, default=0, metavar="G",
                     help="DEC_PRELN workloads: after the timed steps also prefill the batch into a key/value cache and "
                          "time G decode steps (one new token per request and step); reported under \"decode\"")
@@ -74,6 +77,9 @@ def main() -> int:
     if args.tenants or args.slots:
         wl = wl.scaled(name=wl.name + "_scaled", n_tenants=args.tenants or wl.n_tenants,
                        hbm_slots=args.slots or wl.hbm_slots)
+    images = args.images if args.images >= 0 else (500 if wl.name == "hbert_10k" else 0)
+    if images:
+        wl = wl.scaled(n_images=images)
     torch.cuda.set_device(0)
     t0 = time.time()
     ids, lens, x = harness.batch_to_device(wl)
@@ -85,21 +91,32 @@ def main() -> int:
           f"image={pool.image_bytes / 1e6:.2f} MB setup={time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     # A pool with a host tier sees a different batch of tenant ids every step (same lengths and
-    # hidden states, so N is fixed), and the next batch's tenants are prefetched on the copy
-    # stream while the current batch computes (the paper's coarse pipelining, Sec. 6.2).
-    n_batches = args.warmup + 3 * args.steps + 1
+    # hidden states, so N is fixed).  Its requests arrive one by one at the library's request queue,
+    # which forms the batches, runs them in order and prefetches the next batch's tenants on the
+    # copy stream while the current batch computes (the paper's dispatcher rule, Sec. 4.2, and its
+    # coarse-grained pipelining, Sec. 6.2).
+    n_batches = args.warmup + 3 * args.steps + 2
     batches = [ids] if not wl.host_tier else [synth.batch_ids_lens(wl, b)[0] for b in range(n_batches)]
     counter = [0]
+    queue = None
+    if wl.host_tier:
+        queue = hmi.Queue(pool, len(ids), N, max_waiting_batches=2)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        rows = [x[off[r]:off[r + 1]] for r in range(len(ids))]
+
+        def push_batch(b):
+            cur = batches[b % len(batches)]
+            for r in range(len(cur)):
+                assert queue.push(int(cur[r]), rows[r]) is not None
+
+        push_batch(0)
 
     def step():
         b = counter[0]
         counter[0] += 1
         if wl.host_tier:
-            cur = batches[b % len(batches)]
-            nxt = batches[(b + 1) % len(batches)]
-            pool.stack_forward(0, wl.n_layers, x, y, cur, lens)
-            for layer in range(wl.n_layers):
-                pool.prefetch(layer, np.unique(nxt))
+            push_batch(b + 1)       # its first request closes batch b, which is full
+            queue.run()             # batch b; batch b + 1 is prefetched under it
         else:
             pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
 
@@ -263,7 +280,48 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- host tier: what the pipelining buys.  The same kind of steps without any prefetch (every miss is
+    #      met by the forward call itself), and the prefetch traffic alone (nothing to hide it under).
+    tier = None
+    if wl.host_tier:
+        kernels_ms = sum(v["ms"] for v in prof.values()) / args.steps
+        n_probe = max(3, args.steps // 2)
+        torch.cuda.synchronize()
+        s0 = pool.stats()
+        tn = time.perf_counter()
+        for i in range(n_probe):
+            pool.stack_forward(0, wl.n_layers, x, y, batches[(counter[0] + 2 + i) % len(batches)], lens)
+        torch.cuda.synchronize()
+        t_noprefetch = (time.perf_counter() - tn) / n_probe
+        s1 = pool.stats()
+        tcp = time.perf_counter()
+        for i in range(n_probe):
+            for layer in range(wl.n_layers):
+                pool.prefetch(layer, np.unique(batches[(counter[0] + 2 + n_probe + i) % len(batches)]))
+        torch.cuda.synchronize()
+        t_copy = (time.perf_counter() - tcp) / n_probe
+        s2 = pool.stats()
+        t_step = ms_per_step * 1e-3
+        hidden = max(0.0, t_copy + kernels_ms * 1e-3 - t_step)
+        tier = {
+            "batches": "requests pushed one by one into the library's queue; a new batch of tenant ids every step; "
+                       "next batch prefetched during the current one",
+            "hit_rate": round((stats1["hits"] - stats0["hits"]) /
+                              max(1, stats1["hits"] - stats0["hits"] + stats1["misses"] - stats0["misses"]), 4),
+            "h2d_GB_per_s": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / elapsed / 1e9, 2),
+            "h2d_MB_per_step": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / args.steps / 1e6, 1),
+            "without_prefetch": {"hit_rate": round((s1["hits"] - s0["hits"]) / max(1, s1["hits"] - s0["hits"] + s1["misses"] - s0["misses"]), 4),
+                                 "ms_per_step": round(t_noprefetch * 1e3, 4),
+                                 "h2d_MB_per_step": round((s1["bytes_h2d"] - s0["bytes_h2d"]) / n_probe / 1e6, 1)},
+            "copy_alone_ms_per_step": round(t_copy * 1e3, 4),
+            "copy_alone_GB_per_s": round((s2["bytes_h2d"] - s1["bytes_h2d"]) / n_probe / max(t_copy, 1e-9) / 1e9, 2),
+            "kernels_ms_per_step": round(kernels_ms, 4),
+            # share of the shorter of the two (copies, kernels) that runs hidden under the other
+            "overlap_fraction": round(hidden / max(min(t_copy, kernels_ms * 1e-3), 1e-9), 3)}
+
     stats = pool.stats()
+    if queue is not None:
+        queue.close()
     pool.close()
     out = {
         "metric": "mixed-tenant tokens/sec per layer; grouped-GEMM TFLOP/s as % of bf16 MFMA peak",
@@ -272,18 +330,14 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_tenants} tenants, {len(ids)} requests, {N} tokens, "
-                               f"d={wl.d_model} f={wl.d_ff} heads={wl.n_heads} layers={wl.n_layers}",
+                               f"d={wl.d_model} f={wl.d_ff} heads={wl.n_heads} layers={wl.n_layers}"
+                               + (f", {wl.hbm_slots} HBM slots, tenant ids share {wl.n_images} pinned weight sets" if wl.n_images else ""),
                    "block": wl.block, "tenant_popularity": wl.popularity, "distinct_tenants": len(set(ids.tolist()))},
         "ms_per_step_p10_p50_p90": [pct(0.10), pct(0.50), pct(0.90)],
         "step_tflops": round(flops_step / (ms_per_step * 1e-3) / 1e12, 2),
         "step_frac_of_peak": round(flops_step / (ms_per_step * 1e-3) / 1e12 / peak, 4),
         "pool": stats,
-        "host_tier": None if not wl.host_tier else {
-            "batches": "a new batch of tenant ids every step, next batch prefetched during the current one",
-            "hit_rate": round((stats1["hits"] - stats0["hits"]) /
-                              max(1, stats1["hits"] - stats0["hits"] + stats1["misses"] - stats0["misses"]), 4),
-            "h2d_GB_per_s": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / elapsed / 1e9, 2),
-            "h2d_MB_per_step": round((stats1["bytes_h2d"] - stats0["bytes_h2d"]) / args.steps / 1e6, 1)},
+        "host_tier": tier,
         "heads": heads,
         "decode": decode,
         "request_path": pipeline,

@@ -103,6 +103,15 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out);
 int32_t hmi_pool_load_tenant(hmi_pool_t* pool, int32_t tenant_id, int32_t layer,
                              const void* const* tensors, int32_t n_tensors);
 
+/* Pools with host_tier: create instance `tenant_id` with the task parameters of `source_tenant`, all layers (in
+ * the paper instances are created from stored fine-tuned parameters, Sec. 4.1 / Sec. 5.2; here several instances
+ * may be created from one stored set).  The two share one image in pinned host memory, so a tenant id space larger
+ * than the pinned memory can hold still exercises the HBM cache at its real size: in HBM every tenant id has its
+ * own slot, hits, misses and swap-in traffic.  Every layer of `source_tenant` must be loaded and `tenant_id` must
+ * not have parameters yet, else HMI_ERR_TENANT / HMI_ERR_ARG.  Afterwards neither of the two can be loaded again
+ * with hmi_pool_load_tenant (HMI_ERR_ARG).  Takes a free HBM slot if there is one, like hmi_pool_load_tenant. */
+int32_t hmi_pool_alias_tenant(hmi_pool_t* pool, int32_t tenant_id, int32_t source_tenant);
+
 /* ENC_ADAPTER / DEC_ADAPTER pools: register the parameters of `layer` that every tenant shares (the
  * higher transformer layers stay on the GPU and are reused across tenants, Sec. 3.2.2).
  * `tensors`: HOST array of the 12 ENC_POSTLN tensors as HOST pointers, pool dtype, dense
@@ -226,6 +235,54 @@ int32_t hmi_pool_prefetch(hmi_pool_t* pool, int32_t layer, const int32_t* tenant
  * forward calls; bytes_h2d counts swap-in traffic.  Any pointer may be NULL. */
 int32_t hmi_pool_stats(hmi_pool_t* pool, int64_t* hits, int64_t* misses, int64_t* bytes_h2d,
                        int64_t* evictions);
+
+/* ---- Request queue: the batch former and pipelined runner in front of a pool ----
+ *
+ * The paper's dispatcher appends every inference request to the last batch of its input queue and
+ * opens a new batch when the maximum batch size is reached (Sec. 4.2); its scheduler runs the batches
+ * in order and, while one batch computes, already loads the next batch's task parameters on the other
+ * stream (coarse-grained pipelining, Sec. 6.2).  A queue does both for one pool.  Not thread-safe;
+ * calls on a queue and on its pool must come from one thread at a time.  The queue owns its batch
+ * buffers (x and y of max_batch_tokens rows for each of max_waiting_batches + 2 batches). */
+typedef struct hmi_queue hmi_queue_t; /* opaque */
+
+/* max_batch_requests <= the pool's max_requests, max_batch_tokens <= its max_tokens,
+ * 1 <= max_waiting_batches <= 64: batches that may wait to run at any time. */
+int32_t hmi_queue_create(hmi_pool_t* pool, int32_t max_batch_requests, int32_t max_batch_tokens,
+                         int32_t max_waiting_batches, hmi_queue_t** out);
+
+/* One inference request: tenant_id's instance on x_rows, DEVICE [seq_len, d_model] in the pool dtype,
+ * 16-byte aligned.  The rows are not copied here: they must stay valid and unchanged until the request's
+ * batch has been run (hmi_queue_run gathers the rows of all its requests with one kernel on
+ * compute_stream) and that stream has passed the gather.  The request joins the last batch; a new batch is opened when
+ * the last one is full: max_batch_requests requests, or not enough of max_batch_tokens left, or
+ * already hbm_slots distinct tenants and this would be another one.  *ticket identifies the
+ * request.  Errors change nothing: unknown / unloaded tenant -> HMI_ERR_TENANT; seq_len outside
+ * [1, max_batch_tokens] -> HMI_ERR_SHAPE; a new batch is needed while max_waiting_batches are
+ * waiting -> HMI_ERR_CAPACITY (run one, then push again). */
+int32_t hmi_queue_push(hmi_queue_t* queue, int32_t tenant_id, int32_t seq_len, const void* x_rows,
+                       int64_t* ticket);
+
+/* Runs the oldest waiting batch through all layers of the pool (hmi_stack_forward, enqueued on
+ * compute_stream), then, with host_tier, starts bringing every layer of the tenants of the next
+ * waiting batch into HBM on the copy stream (hmi_pool_prefetch), so that the copies run under this
+ * batch's kernels.  *batch (may be NULL) = the number of the batch that ran, counted from 0 in the
+ * order the batches were opened, or -1 if none was waiting; *n_requests (may be NULL) its size. */
+int32_t hmi_queue_run(hmi_queue_t* queue, int64_t* batch, int32_t* n_requests);
+
+/* Copies the output rows of one request, DEVICE [seq_len, d_model], to y_rows (enqueued on
+ * compute_stream).  The request's batch must have run, and its results are held until
+ * max_waiting_batches + 1 later batches have been opened; otherwise HMI_ERR_ARG. */
+int32_t hmi_queue_fetch(hmi_queue_t* queue, int64_t ticket, void* y_rows);
+
+/* Batches waiting to run (the open one counts if it holds a request). */
+int32_t hmi_queue_waiting(const hmi_queue_t* queue);
+
+/* Reason of the last error on this queue. */
+const char* hmi_queue_last_error(const hmi_queue_t* queue);
+
+/* Waits for compute_stream, frees the batch buffers.  Destroy the queue before its pool.  NULL is fine. */
+int32_t hmi_queue_destroy(hmi_queue_t* queue);
 
 /* Per-kernel timing for measurement: while enabled, every kernel the forward calls launch
  * is bracketed by HIP events on compute_stream.  hmi_pool_profile_read waits for the

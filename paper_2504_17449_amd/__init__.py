@@ -21,11 +21,13 @@ HMI_OK, HMI_ERR_ARG, HMI_ERR_OOM, HMI_ERR_TENANT, HMI_ERR_SHAPE, HMI_ERR_CAPACIT
 HMI_F32, HMI_BF16 = 0, 1
 HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER, HMI_BLOCK_DEC_ADAPTER = 0, 1, 2, 3, 4, 5
 
-EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward",
+EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_alias_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward",
            "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_plot_aggregate", "hmi_layer_forward", "hmi_layer_forward_static", "hmi_stack_forward",
            "hmi_get_route",
            "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
-           "hmi_pool_destroy"]
+           "hmi_pool_destroy",
+           "hmi_queue_create", "hmi_queue_push", "hmi_queue_run", "hmi_queue_fetch", "hmi_queue_waiting",
+           "hmi_queue_last_error", "hmi_queue_destroy"]
 
 
 class hmi_pool_config_t(C.Structure):
@@ -53,6 +55,8 @@ def _load() -> C.CDLL:
     lib.hmi_pool_create.restype = i32
     lib.hmi_pool_load_tenant.argtypes = [vp, i32, i32, C.POINTER(vp), i32]
     lib.hmi_pool_load_tenant.restype = i32
+    lib.hmi_pool_alias_tenant.argtypes = [vp, i32, i32]
+    lib.hmi_pool_alias_tenant.restype = i32
     lib.hmi_pool_load_shared.argtypes = [vp, i32, C.POINTER(vp), i32]
     lib.hmi_pool_load_shared.restype = i32
     lib.hmi_pool_load_head.argtypes = [vp, i32, vp, vp, i32, i32]
@@ -89,6 +93,20 @@ def _load() -> C.CDLL:
     lib.hmi_last_error.restype = C.c_char_p
     lib.hmi_pool_destroy.argtypes = [vp]
     lib.hmi_pool_destroy.restype = i32
+    lib.hmi_queue_create.argtypes = [vp, i32, i32, i32, C.POINTER(vp)]
+    lib.hmi_queue_create.restype = i32
+    lib.hmi_queue_push.argtypes = [vp, i32, i32, vp, C.POINTER(i64)]
+    lib.hmi_queue_push.restype = i32
+    lib.hmi_queue_run.argtypes = [vp, C.POINTER(i64), pi32]
+    lib.hmi_queue_run.restype = i32
+    lib.hmi_queue_fetch.argtypes = [vp, i64, vp]
+    lib.hmi_queue_fetch.restype = i32
+    lib.hmi_queue_waiting.argtypes = [vp]
+    lib.hmi_queue_waiting.restype = i32
+    lib.hmi_queue_last_error.argtypes = [vp]
+    lib.hmi_queue_last_error.restype = C.c_char_p
+    lib.hmi_queue_destroy.argtypes = [vp]
+    lib.hmi_queue_destroy.restype = i32
     return lib
 
 
@@ -130,6 +148,10 @@ def hmi_pool_load_tenant(pool: int, tenant_id: int, layer: int, tensors: Sequenc
     keep = [np.ascontiguousarray(t) for t in tensors]
     arr = (C.c_void_p * len(keep))(*[t.ctypes.data for t in keep])
     return lib.hmi_pool_load_tenant(pool, tenant_id, layer, arr, len(keep))
+
+
+def hmi_pool_alias_tenant(pool: int, tenant_id: int, source_tenant: int) -> int:
+    return lib.hmi_pool_alias_tenant(pool, tenant_id, source_tenant)
 
 
 def hmi_pool_load_shared(pool: int, layer: int, tensors: Sequence[np.ndarray]) -> int:
@@ -246,6 +268,43 @@ def hmi_pool_destroy(pool: Optional[int]) -> int:
     return lib.hmi_pool_destroy(pool)
 
 
+def hmi_queue_create(pool: int, max_batch_requests: int, max_batch_tokens: int, max_waiting_batches: int):
+    """-> (status, queue handle or None)."""
+    out = C.c_void_p()
+    rc = lib.hmi_queue_create(pool, max_batch_requests, max_batch_tokens, max_waiting_batches, C.byref(out))
+    return rc, (out.value if rc == HMI_OK else None)
+
+
+def hmi_queue_push(queue: int, tenant_id: int, seq_len: int, x_rows_ptr: int):
+    """-> (status, ticket)."""
+    t = C.c_int64(-1)
+    rc = lib.hmi_queue_push(queue, tenant_id, seq_len, x_rows_ptr, C.byref(t))
+    return rc, t.value
+
+
+def hmi_queue_run(queue: int):
+    """-> (status, batch number or -1, its number of requests)."""
+    b, n = C.c_int64(-1), C.c_int32(0)
+    rc = lib.hmi_queue_run(queue, C.byref(b), C.byref(n))
+    return rc, b.value, n.value
+
+
+def hmi_queue_fetch(queue: int, ticket: int, y_rows_ptr: int) -> int:
+    return lib.hmi_queue_fetch(queue, ticket, y_rows_ptr)
+
+
+def hmi_queue_waiting(queue: int) -> int:
+    return lib.hmi_queue_waiting(queue)
+
+
+def hmi_queue_last_error(queue: Optional[int]) -> str:
+    return (lib.hmi_queue_last_error(queue) or b"").decode()
+
+
+def hmi_queue_destroy(queue: Optional[int]) -> int:
+    return lib.hmi_queue_destroy(queue)
+
+
 # ---------------------------------------------------------------- convenience wrapper
 
 class Pool:
@@ -264,6 +323,9 @@ class Pool:
 
     def load_tenant(self, tenant_id: int, layer: int, tensors) -> None:
         self._check(hmi_pool_load_tenant(self.h, tenant_id, layer, tensors))
+
+    def alias_tenant(self, tenant_id: int, source_tenant: int) -> None:
+        self._check(hmi_pool_alias_tenant(self.h, tenant_id, source_tenant))
 
     def load_shared(self, layer: int, tensors) -> None:
         self._check(hmi_pool_load_shared(self.h, layer, tensors))
@@ -325,6 +387,52 @@ class Pool:
     def close(self) -> None:
         if self.h is not None:
             hmi_pool_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Queue:
+    """Owns one request queue in front of a Pool; raises HmiError on any non-zero status except a full queue."""
+
+    def __init__(self, pool: Pool, max_batch_requests: int, max_batch_tokens: int, max_waiting_batches: int = 2):
+        self.pool = pool
+        rc, h = hmi_queue_create(pool.h, max_batch_requests, max_batch_tokens, max_waiting_batches)
+        if rc != HMI_OK:
+            raise HmiError(rc, "hmi_queue_create failed")
+        self.h = h
+
+    def _check(self, rc: int) -> None:
+        if rc != HMI_OK:
+            raise HmiError(rc, hmi_queue_last_error(self.h))
+
+    def push(self, tenant_id: int, x_rows):
+        """x_rows: torch tensor [seq_len, d] on the device.  -> ticket, or None when the queue is full (run a batch first)."""
+        rc, ticket = hmi_queue_push(self.h, tenant_id, x_rows.shape[0], x_rows.data_ptr())
+        if rc == HMI_ERR_CAPACITY:
+            return None
+        self._check(rc)
+        return ticket
+
+    def run(self):
+        """-> (batch number or -1, number of requests)."""
+        rc, b, n = hmi_queue_run(self.h)
+        self._check(rc)
+        return b, n
+
+    def fetch(self, ticket: int, y_rows) -> None:
+        self._check(hmi_queue_fetch(self.h, ticket, y_rows.data_ptr()))
+
+    def waiting(self) -> int:
+        return hmi_queue_waiting(self.h)
+
+    def close(self) -> None:
+        if self.h is not None:
+            hmi_queue_destroy(self.h)
             self.h = None
 
     def __del__(self):

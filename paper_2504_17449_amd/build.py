@@ -14,7 +14,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhmi.so")
-SOURCES = ["pool.hip", "router.hip", "gemm_bf16.hip", "gemm_bf16_p256.hip", "gemm_bf16_skinny.hip", "adapter_bf16.hip", "gemm_f32.hip",
+SOURCES = ["pool.hip", "queue.hip", "router.hip", "gemm_bf16.hip", "gemm_bf16_p256.hip", "gemm_bf16_skinny.hip", "adapter_bf16.hip", "gemm_f32.hip",
            "layernorm.hip", "attention.hip", "head.hip", "kv_cache.hip", "plot.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -41,18 +41,9 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
   return __builtin_bit_cast(uint16_t, b);
 }
 
-// GELU(x) = x * Phi(x) with erf from the Abramowitz-Stegun 7.1.26 rational form
-// (|error| <= 1.5e-7, far below bf16 resolution), branch-free: one rcp, one exp.
-__device__ __forceinline__ float gelu_erf(float x) {
-  const float z = fabsf(x) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float p = fmaf(t, 1.061405429f, -1.453152027f);
-  p = fmaf(t, p, 1.421413741f);
-  p = fmaf(t, p, -0.284496736f);
-  p = fmaf(t, p, 0.254829592f);
-  const float e = 1.0f - p * t * __expf(-z * z);     // erf(|x| / sqrt 2)
-  return 0.5f * x + 0.5f * fabsf(x) * e;             // 0.5 x (1 + sign(x) e)
-}
+// Exact GELU x * Phi(x), as in the skinny and fp32 kernels (these tiles serve odd shapes; their
+// epilogue is not on the measured path).
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
 // Which tile does this workgroup own.  Returns false for padding workgroups.
 struct TileCoord { int mt, n0, seg, row0, rows; size_t slot_base; };

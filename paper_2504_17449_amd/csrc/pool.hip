@@ -8,6 +8,7 @@
 // one batch mixes tenants and is executed in one set of launches (Sec. 6.3).
 #include "../../include/hmi.h"
 #include "hmi_kernels.h"
+#include "pool_internal.h"
 
 #include <algorithm>
 #include <cstdarg>
@@ -125,6 +126,8 @@ struct hmi_pool {
   std::vector<int32_t> free_slots;
   uint64_t clock = 0;
   std::vector<char*> host_img;       // [tenant] pinned, all layers (host tier)
+  std::vector<int32_t> alias_of;     // [tenant] the tenant whose pinned image this one shares (-1: its own)
+  std::vector<int32_t> alias_count;  // [tenant] tenants that share this one's image
   std::vector<char*> arenas;
   char* arena_cur = nullptr;
   int arena_left = 0;
@@ -164,7 +167,7 @@ struct hmi_pool {
   int32_t* d_head_meta = nullptr;      // [tenant] {n_classes, per_token}
   std::vector<uint8_t> head_loaded;
   std::vector<int32_t> last_distinct;  // tenants of the last routed batch
-  int last_n_mtiles[2] = {0, 0};       // its m-tile counts
+  int last_n_mtiles[4] = {0, 0, 0, 0};  // its m-tile counts
   int last_N = 0;                      // and rows
   float* w_scores = nullptr;           // [max_tokens, kHeadCols] raw scores
 
@@ -477,7 +480,11 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   p->slot_fwd.assign(c.hbm_slots, 0);
   p->slot_copy.assign(c.hbm_slots, 0);
   for (int s = c.hbm_slots - 1; s >= 0; --s) p->free_slots.push_back(s);
-  if (c.host_tier) p->host_img.assign(c.max_tenants, nullptr);
+  if (c.host_tier) {
+    p->host_img.assign(c.max_tenants, nullptr);
+    p->alias_of.assign(c.max_tenants, -1);
+    p->alias_count.assign(c.max_tenants, 0);
+  }
   p->mark.assign(c.max_tenants, 0);
   p->tok_count.assign(c.max_tenants, 0);
   p->distinct.reserve(c.max_requests);
@@ -500,18 +507,19 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   const size_t MT = (size_t)c.max_tokens;
   const size_t max_tiles0 = MT / p->tile_m[0] + Rm + 1;
   const size_t max_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + Rm + 1 : 0;
+  const size_t max_tiles2 = p->bf16 ? MT / 256 + Rm + 1 : 0, max_tiles3 = p->bf16 ? Rm + 1 : 0;
   size_t n_i32 = 3 * (size_t)Rm            // ids, lens, req_slot
                  + 3 * (size_t)Rm          // req_tenant, kv_slot, kv_pos
                  + Rm + (Rm + 1)           // perm, tok_off
                  + 2 * (size_t)Rm          // seg_tenant, seg_slot
                  + 2 * ((size_t)Rm + 1)    // seg_req_off, seg_tok_off
                  + MT                      // row_src
-                 + 2 * (max_tiles0 + max_tiles1) + 4   // tile lists + counters
+                 + 2 * (max_tiles0 + max_tiles1 + max_tiles2 + max_tiles3) + 8   // tile lists + counters
                  + kGemmSchedInts;
   const bool dense = composite;
   const size_t dense_segs = MT / kDenseSegRows + 2;
   const size_t dense_tiles0 = MT / p->tile_m[0] + 2, dense_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + 2 : 0;
-  if (dense) n_i32 += 2 * dense_segs + 1 + MT + 2 * (dense_tiles0 + dense_tiles1);
+  if (dense) n_i32 += 2 * dense_segs + 1 + MT + 2 * (dense_tiles0 + dense_tiles1) + 4;
   CREATE_TRY(hipMalloc(&p->d_idx, n_i32 * sizeof(int32_t)));
   CREATE_TRY(hipMemset(p->d_idx, 0, n_i32 * sizeof(int32_t)));
   int32_t* q = p->d_idx;
@@ -526,7 +534,12 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   rt.tile_seg[0] = take(max_tiles0); rt.tile_row0[0] = take(max_tiles0);
   rt.tile_seg[1] = max_tiles1 ? take(max_tiles1) : nullptr;
   rt.tile_row0[1] = max_tiles1 ? take(max_tiles1) : nullptr;
-  rt.n_segments = take(1); rt.n_tiles[0] = take(1); rt.n_tiles[1] = take(1);
+  rt.tile_seg[2] = max_tiles2 ? take(max_tiles2) : nullptr;
+  rt.tile_row0[2] = max_tiles2 ? take(max_tiles2) : nullptr;
+  rt.tile_seg[3] = max_tiles3 ? take(max_tiles3) : nullptr;
+  rt.tile_row0[3] = max_tiles3 ? take(max_tiles3) : nullptr;
+  rt.n_segments = take(1);
+  for (int k = 0; k < 4; ++k) rt.n_tiles[k] = take(1);
   rt.gemm_sched = take(kGemmSchedInts);
   rt.tile_m[0] = p->tile_m[0]; rt.tile_m[1] = p->tile_m[1];
   rt.key_bits = bits_for(c.max_tenants);
@@ -544,8 +557,16 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
     rd.tile_seg[0] = take(dense_tiles0); rd.tile_row0[0] = take(dense_tiles0);
     rd.tile_seg[1] = dense_tiles1 ? take(dense_tiles1) : nullptr;
     rd.tile_row0[1] = dense_tiles1 ? take(dense_tiles1) : nullptr;
+    // lists 2 and 3 of the dense route: its segments are multiples of 256 rows except the last, so the
+    // tiles of more than 128 rows are a prefix of list 0, and the one short tile is written by the router
+    rd.tile_seg[2] = rd.tile_seg[0]; rd.tile_row0[2] = rd.tile_row0[0];
+    rd.tile_seg[3] = take(1); rd.tile_row0[3] = take(1);
     rt.dense_seg_tok_off = rd.seg_tok_off;
     rt.dense_n_segments = rd.n_segments;
+    rt.dense_short_seg = rd.tile_seg[3];
+    rt.dense_short_row0 = rd.tile_row0[3];
+    rd.dense_seg_tok_off = nullptr; rd.dense_n_segments = nullptr;
+    rd.dense_short_seg = nullptr; rd.dense_short_row0 = nullptr;
     std::vector<int32_t> h(MT);
     for (size_t i = 0; i < MT; ++i) h[i] = (int32_t)i;
     CREATE_TRY(hipMemcpy(rd.row_src, h.data(), MT * sizeof(int32_t), hipMemcpyHostToDevice));
@@ -595,6 +616,8 @@ int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
   const int L = p->cfg.n_layers;
 
   if (p->cfg.host_tier) {
+    if (p->alias_of[tenant] >= 0 || p->alias_count[tenant] > 0)
+      return fail(p, HMI_ERR_ARG, "tenant %d shares its image with other tenants: it cannot be loaded again", tenant);
     if (!p->host_img[tenant]) {
       if (p->arena_left == 0) {
         char* a = nullptr;
@@ -645,6 +668,37 @@ int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
   p->copy_done.record(p->copy);
   p->slot_valid[(size_t)slot * L + layer] = 1;
   p->loaded[(size_t)tenant * L + layer] = 1;
+  return HMI_OK;
+}
+
+int32_t hmi_pool_alias_tenant(hmi_pool_t* p, int32_t tenant, int32_t source) {
+  if (!p) return HMI_ERR_ARG;
+  const hmi_pool_config_t& c = p->cfg;
+  if (!c.host_tier) return fail(p, HMI_ERR_ARG, "tenants can share an image only in a pool with a host tier");
+  if (tenant < 0 || tenant >= c.max_tenants || source < 0 || source >= c.max_tenants)
+    return fail(p, HMI_ERR_TENANT, "tenant %d or %d outside [0,%d)", tenant, source, c.max_tenants);
+  if (tenant == source) return fail(p, HMI_ERR_ARG, "a tenant cannot share its own image");
+  const int L = c.n_layers;
+  if (p->alias_of[source] >= 0) source = p->alias_of[source];
+  for (int l = 0; l < L; ++l)
+    if (!p->loaded[(size_t)source * L + l]) return fail(p, HMI_ERR_TENANT, "tenant %d (layer %d) is not loaded", source, l);
+  if (p->host_img[tenant]) return fail(p, HMI_ERR_ARG, "tenant %d already has parameters", tenant);
+  HIP_TRY(p, hipSetDevice(c.device));
+  p->host_img[tenant] = p->host_img[source];
+  p->alias_of[tenant] = source;
+  ++p->alias_count[source];
+  for (int l = 0; l < L; ++l) p->loaded[(size_t)tenant * L + l] = 1;
+  if (!p->free_slots.empty()) {     // like a loaded tenant, it takes a free HBM slot while there is one
+    const int slot = acquire_slot(p, tenant, 0);
+    const int64_t before = p->bytes_h2d;
+    for (int l = 0; l < L; ++l) {
+      if (p->slot_valid[(size_t)slot * L + l]) continue;     // a whole-tenant copy brought every layer
+      int32_t rc = enqueue_swap_in(p, tenant, slot, l);
+      if (rc != HMI_OK) return rc;
+    }
+    p->bytes_h2d = before;          // initial placement is not swap traffic
+    p->copy_done.record(p->copy);
+  }
   return HMI_OK;
 }
 
@@ -707,7 +761,7 @@ int32_t hmi_head_forward(hmi_pool_t* p, const void* h, float* scores, int32_t* l
   g.pool = p->d_heads; g.slot_stride = p->head_stride;
   g.w_off = 0; g.b_off = (size_t)kHeadCols * c.d_model * p->esize;
   g.n_out = kHeadCols; g.k = c.d_model; g.n_rows = p->last_N; g.epi = EPI_BIAS;
-  g.n_mtiles_list[0] = p->last_n_mtiles[0]; g.n_mtiles_list[1] = p->last_n_mtiles[1];
+  for (int k = 0; k < 4; ++k) g.n_mtiles_list[k] = p->last_n_mtiles[k];
   g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
   if (p->bf16) launch_gemm_bf16(g, rh, p->compute); else launch_gemm_f32(g, rh, p->compute);
   HeadArgs a{};
@@ -843,10 +897,12 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
 
   // ---- residency of the first layer: hits first (so they cannot be chosen as victims)
   const uint64_t now = ++p->clock;
-  int n_mtiles[2] = {0, 0};
+  int n_mtiles[4] = {0, 0, 0, 0};
   for (int t : p->distinct) {
     n_mtiles[0] += (p->tok_count[t] + p->tile_m[0] - 1) / p->tile_m[0];
     if (p->tile_m[1]) n_mtiles[1] += (p->tok_count[t] + p->tile_m[1] - 1) / p->tile_m[1];
+    n_mtiles[2] += tiles_over_128(p->tok_count[t]);
+    n_mtiles[3] += short_last_tile(p->tok_count[t]);
     const int s = p->slot_of_tenant[t];
     if (s >= 0) p->slot_stamp[s] = now;
   }
@@ -916,7 +972,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
   HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
   p->last_R = R;
   p->last_distinct.assign(p->distinct.begin(), p->distinct.end());   // within the reserved capacity
-  p->last_n_mtiles[0] = n_mtiles[0]; p->last_n_mtiles[1] = n_mtiles[1];
+  for (int k = 0; k < 4; ++k) p->last_n_mtiles[k] = n_mtiles[k];
   p->last_N = (int)N;
 
   const int d = c.d_model, f = c.d_ff;
@@ -956,9 +1012,10 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       g.resid_f32 = resid_f32; g.out_f32 = out_f32; g.C2 = C2;
       g.pool = p->d_pool; g.slot_stride = p->slot_stride;
       g.w_off = lay + p->tl[tw].off; g.b_off = lay + p->tl[tb].off;
-      g.n_out = n_out; g.k = k; g.n_rows = (int)N; g.epi = epi; g.n_mtiles_list[0] = n_mtiles[0]; g.n_mtiles_list[1] = n_mtiles[1];
+      g.n_out = n_out; g.k = k; g.n_rows = (int)N; g.epi = epi;
+      for (int i = 0; i < 4; ++i) g.n_mtiles_list[i] = n_mtiles[i];
       g.which_tiles = 0; g.n_mtiles = n_mtiles[0];
-      ProfSpan ps(p, HMI_KERNEL_GEMM);
+          ProfSpan ps(p, HMI_KERNEL_GEMM);
       if (p->bf16) launch_gemm_bf16(g, rt, s); else launch_gemm_f32(g, rt, s);
     };
     auto lnorm = [&](const void* in, bool in_f32, float* out_f32, void* out_st, int tg, int tb) {
@@ -982,8 +1039,13 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       g.n_out = n_out; g.k = k; g.n_rows = (int)N; g.epi = epi;
       g.n_mtiles_list[0] = (int)((N + p->tile_m[0] - 1) / p->tile_m[0]);
       g.n_mtiles_list[1] = p->tile_m[1] ? (int)((N + p->tile_m[1] - 1) / p->tile_m[1]) : 0;
+      {   // pseudo-segments of kDenseSegRows rows, the last one shorter
+        const int whole = (int)(N / kDenseSegRows), rest = (int)(N % kDenseSegRows);
+        g.n_mtiles_list[2] = whole * (kDenseSegRows / 256) + tiles_over_128(rest);
+        g.n_mtiles_list[3] = short_last_tile(rest);
+      }
       g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
-      ProfSpan ps(p, HMI_KERNEL_GEMM);
+          ProfSpan ps(p, HMI_KERNEL_GEMM);
       if (p->bf16) launch_gemm_bf16(g, p->rt_dense, s); else launch_gemm_f32(g, p->rt_dense, s);
     };
     auto slnorm = [&](const void* in, bool in_f32, const void* in2, float* out_f32, void* out_st, int tg, int tb,
@@ -1288,6 +1350,19 @@ int32_t hmi_pool_profile_read(hmi_pool_t* p, double* ms, int64_t* launches) {
   p->spans.clear();
   return HMI_OK;
 }
+
+}  // extern "C"
+
+const hmi_pool_config_t* hmi_internal_config(const hmi_pool_t* p) { return &p->cfg; }
+hipStream_t hmi_internal_compute_stream(const hmi_pool_t* p) { return p->compute; }
+bool hmi_internal_tenant_ready(const hmi_pool_t* p, int32_t tenant) {
+  if (tenant < 0 || tenant >= p->cfg.max_tenants) return false;
+  for (int l = 0; l < p->cfg.n_layers; ++l)
+    if (!p->loaded[(size_t)tenant * p->cfg.n_layers + l]) return false;
+  return true;
+}
+
+extern "C" {
 
 int64_t hmi_pool_image_bytes(const hmi_pool_t* p) { return p ? (int64_t)p->image_bytes : 0; }
 

@@ -36,7 +36,10 @@ def load_tenants(pool: Pool, wl: synth.Workload, tenants: Optional[Iterable[int]
         for t in tenants:
             w, b = synth.head_tensors(wl, t, raw=True)
             pool.load_head(t, w, b, synth.head_spec(wl, t)[1])
-    todo = [(t, l) for t in tenants
+    # tenants that share another tenant's weight set (wl.n_images > 0) are created from it after it is loaded
+    owners = sorted({synth.image_of(wl, t) for t in tenants})
+    sharers = [t for t in tenants if synth.image_of(wl, t) != t]
+    todo = [(t, l) for t in owners
             for l in range(wl.n_layers)]
 
     def gen(tl):
@@ -46,6 +49,8 @@ def load_tenants(pool: Pool, wl: synth.Workload, tenants: Optional[Iterable[int]
     with ThreadPoolExecutor(workers) as ex:
         for t, l, tensors in ex.map(gen, todo):
             pool.load_tenant(t, l, tensors)
+    for t in sharers:
+        pool.alias_tenant(t, synth.image_of(wl, t))
 
 
 def batch_to_device(wl: synth.Workload, batch: int = 0, device: int = 0

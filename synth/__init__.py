@@ -10,5 +10,5 @@ from .inputs import (  # noqa: F401
     BLOCK_FFN, BLOCK_ENC_POSTLN, BLOCK_DEC_PRELN, BLOCK_ADAPTER, BLOCK_ENC_ADAPTER, BLOCK_DEC_ADAPTER,
     shared_specs, shared_tensors, shared_storage, head_spec, head_tensors, plot_table, plot_fragment_ids,
     Workload, WORKLOADS, tensor_specs, tenant_tensors, tenant_storage, hidden_states, batch_ids_lens,
-    round_to_storage, to_storage_bytes, storage_to_f64,
+    round_to_storage, to_storage_bytes, storage_to_f64, image_of,
 )

@@ -53,6 +53,8 @@ class Workload:
     seed: int = 0
     adapter_rank: int = 0  # BLOCK_ENC_ADAPTER: bottleneck width of the per-tenant adapter
     max_classes: int = 0   # > 0: every tenant also owns an output head with at most this many classes
+    n_images: int = 0      # > 0: only this many distinct weight sets exist; tenant t owns set t % n_images
+                           # (a pinned-host pool that cannot hold one image per tenant id: ids share images)
 
     def scaled(self, **kw) -> "Workload":
         """Same recipe at another size (tests use reduced tenant / request counts)."""
@@ -208,8 +210,15 @@ def _gen(seed: int, tag: int, a: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[(int(seed) << 8) | int(tag), int(a)]))
 
 
+def image_of(wl: Workload, tenant: int) -> int:
+    """The weight set a tenant id owns: its own, or (n_images > 0) the one it shares with the ids congruent to it."""
+    return tenant % wl.n_images if wl.n_images > 0 and 0 <= tenant < SHARED else tenant
+
+
 def _tensor(wl: Workload, tenant: int, layer: int, idx: int, shape, kind: str, raw: bool):
     n = int(np.prod(shape))
+    if layer != _HEAD_LAYER:
+        tenant = image_of(wl, tenant)
     off = _offset(wl.seed, _TAG_WEIGHT, tenant, layer, idx, n)
     v32, vraw = _master(wl.seed, wl.dtype, 0.02)
     if kind == "g":      # LayerNorm gain 1 + N(0, 0.02): small, recomputed and re-rounded

@@ -512,6 +512,62 @@ def test_seeded_random_small_shapes(hmi, seed):
     run_case(hmi, small(block, "bf16", **kw), slack=7 * (seed % 2))    # odd seeds: a pool larger than the batch
 
 
+def round_to_bf16(a) -> np.ndarray:
+    """fp32 values rounded to the nearest bf16 (ties to even), returned as fp32."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32)
+
+
+def test_gelu_of_the_persistent_gemm_alone_on_a_grid(hmi):
+    """The persistent bf16 GEMM evaluates GELU with a polynomial instead of erf.  This isolates it
+    through the C ABI: a pre-LN decoder pool whose attention weights, W1 and all biases but b1 are zero and whose
+    W2 is the identity gives, for x = 0, y[row, j] = GELU(b1[j]) exactly as the kernel stored it (one non-zero
+    product per output, so nothing else rounds).  b1 is a grid over [-9, 9] (four tenants, 1 024 values, bf16
+    exact), beyond the point |x| = 4 where the polynomial is clamped.  Held to the polynomial's stated bound:
+    |error| <= 2e-4 from the fit, plus the bf16 rounding of the stored value (one ulp allowed)."""
+    from paper_2504_17449_amd import harness
+    d = 256
+    wl = small(synth.BLOCK_DEC_PRELN, "bf16", d_model=d, d_ff=d, n_heads=4, n_tenants=4, hbm_slots=4)
+    grid = round_to_bf16(np.concatenate([np.linspace(-9.0, 9.0, 1000), [-4.0, 4.0, 0.0, -0.0], np.linspace(-0.02, 0.02, 20)])
+                         .astype(np.float32))
+    assert grid.size == 4 * d
+    zeros = lambda *shape: np.zeros(shape, np.float32)
+    ids = np.repeat(np.arange(4, dtype=np.int32), 3)            # 12 requests of 256 rows: enough rows for the persistent kernel
+    lens = np.full(12, 256, np.int32)
+    pool = harness.create_pool(wl, max_requests=12, max_tokens=int(lens.sum()))
+    weights = {}
+    try:
+        for t in range(4):
+            w = {"wqkv": zeros(3 * d, d), "bqkv": zeros(3 * d), "wo": zeros(d, d), "bo": zeros(d),
+                 "ln1_g": np.ones(d, np.float32), "ln1_b": zeros(d), "w1": zeros(d, d), "b1": grid[t * d:(t + 1) * d],
+                 "w2": np.eye(d, dtype=np.float32), "b2": zeros(d), "ln2_g": np.ones(d, np.float32), "ln2_b": zeros(d)}
+            weights[t] = w
+            names = [n for n, _, _ in synth.tensor_specs(wl)]
+            pool.load_tenant(t, 0, [synth.to_storage_bytes(w[n], "bf16") for n in names])
+        x = torch.zeros(int(lens.sum()), d, dtype=torch.bfloat16, device="cuda")
+        y = torch.empty_like(x)
+        pool.forward(0, x, y, ids, lens)
+        torch.cuda.synchronize()
+        y_gpu = harness.device_to_f64(y)
+    finally:
+        pool.close()
+    wof = lambda t: {k: v.astype(np.float64) for k, v in weights[t].items()}
+    y_ref = O.layer_forward(wl.block, np.zeros((int(lens.sum()), d)), ids, lens, wof, wl.n_heads, wl.ln_eps)
+    g = y_ref                                                    # = GELU(b1[j]) in every row of the tenant
+    np.testing.assert_allclose(y_ref[0], O.gelu(grid[:d].astype(np.float64)), rtol=0, atol=1e-12)
+    err = np.abs(y_gpu - y_ref)
+    bound = 2e-4 + 2.0 ** -8 * np.abs(g) + 1e-6                  # fit + bf16 rounding (one ulp) + fp32 evaluation
+    worst = int(np.argmax(err - bound))
+    print(f"  GELU grid: max |error| {err.max():.3e}, worst excess over the bound {(err - bound).max():.3e} "
+          f"at x = {grid[(ids[worst // d // 256] * d) + worst % d]:.4f}", flush=True)
+    assert (err <= bound).all()
+    # rows of one tenant are identical, and the negative tail is not flushed to zero before the clamp
+    assert np.array_equal(y_gpu[0], y_gpu[255])
+    i3 = int(np.argmin(np.abs(grid + 3.0)))                      # GELU(-3) = -4.05e-3
+    assert y_gpu[(i3 // d) * 3 * 256, i3 % d] < -3.5e-3
+
+
 def test_bert_ffn_full_size_every_request(hmi):
     """The benchmarked configuration (64 tenants, 256 requests of 128 tokens, d = 768, f = 3072) as bench.py
     runs it, all 32 768 rows against the oracle."""
