@@ -78,13 +78,23 @@ __global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinn
   const int q = row_split ? item >> 2 : item;
   const int nb = q % NB, t = q / NB;
   const int sub_begin = row_split ? (item & 3) : 0, sub_end = row_split ? sub_begin + 1 : 4;
-  const int seg = rt.tile_seg[g.which_tiles][t];
-  const int seg_end = rt.seg_tok_off[seg + 1];
+  // the route of the shared parameters needs no lookups: tiles in row order, identity row map, slot 0
+  const bool ident = rt.identity != 0;
+  int seg_end, tile_row0;
+  size_t slot_base = 0;
+  if (ident) {
+    tile_row0 = t * rt.tile_m[g.which_tiles];
+    seg_end = min(g.n_rows, (tile_row0 / kDenseSegRows + 1) * kDenseSegRows);
+  } else {
+    const int seg = rt.tile_seg[g.which_tiles][t];
+    seg_end = rt.seg_tok_off[seg + 1];
+    tile_row0 = rt.tile_row0[g.which_tiles][t];
+    slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
+  }
   for (int sub = sub_begin; sub < sub_end; ++sub) {
-  const int row0 = rt.tile_row0[g.which_tiles][t] + SK * sub;
+  const int row0 = tile_row0 + SK * sub;
   const int rows = min(SK, seg_end - row0);
   if (rows <= 0) return;
-  const size_t slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
   const int n0 = nb * SK;
   const int kb = g.k * 2;                               // bytes of a weight row
   const char* Wp = g.pool + slot_base + g.w_off + (size_t)n0 * kb;
@@ -102,10 +112,11 @@ __global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinn
   for (int i = 0; i < 4; ++i) {
     const int row = 8 * i + (lane >> 3);
     w_off[i] = (uint32_t)row * (uint32_t)kb + (((lane & 7) ^ swz_w(row)) << 4);
-    x_off[i] = (uint32_t)rt.row_src[row0 + min(row, rows - 1)] * (uint32_t)(g.lda * 2) + (((lane & 7) ^ swz_a(row)) << 4);
+    const int xr = row0 + min(row, rows - 1);
+    x_off[i] = (uint32_t)(ident ? xr : rt.row_src[xr]) * (uint32_t)(g.lda * 2) + (((lane & 7) ^ swz_a(row)) << 4);
   }
   unsigned char* ring = smem + wave * WAVE_LDS;
-  const int my_row = rt.row_src[row0 + min(l32, rows - 1)];
+  const int my_row = ident ? row0 + min(l32, rows - 1) : rt.row_src[row0 + min(l32, rows - 1)];
   const int rw = perm_w(l32);
   const int fw_base = rw * 128 + ((lh ^ swz_w(rw)) << 4);
   const int fx_base = X_RING + l32 * 128 + ((lh ^ swz_a(l32)) << 4);

@@ -24,14 +24,11 @@ struct Route {
   int32_t* seg_tok_off;       // [G+1] segment -> first sorted row
   int32_t* row_src;           // [N]   sorted row -> original row
   int32_t* n_segments;        // [1]
-  // m-tile work lists (rows of one tile never cross a segment).  Lists 0 and 1: every segment cut
-  // into tiles of tile_m[0] / tile_m[1] rows.  Lists 2 and 3 (bf16 pools) cut a segment into 256-row
-  // tiles as list 0 does, but keep a last tile of at most 128 rows apart: list 2 holds the tiles of
-  // more than 128 rows, list 3 the short last tiles (at most one per segment).
-  int32_t* tile_seg[4];       // [tiles] tile -> segment
-  int32_t* tile_row0[4];      // [tiles] tile -> first sorted row
-  int32_t* n_tiles[4];        // [1]
-  int32_t tile_m[2];          // tile heights of lists 0 and 1 (0 = list unused)
+  // m-tile work lists for two tile heights (rows of one tile never cross a segment)
+  int32_t* tile_seg[2];       // [tiles] tile -> segment
+  int32_t* tile_row0[2];      // [tiles] tile -> first sorted row
+  int32_t* n_tiles[2];        // [1]
+  int32_t tile_m[2];          // tile heights (0 = list unused)
   int32_t key_bits;           // bits needed for the largest tenant id (radix passes = bits/4)
   // scratch of the persistent GEMM: per XCD a tile-claim counter [0..7] and a count of finished
   // workgroups [8..15], then one mailbox per workgroup; all zero between launches
@@ -47,8 +44,11 @@ struct Route {
   // shorter), which all name slot 0; its tile lists and row map do not depend on the batch.
   int32_t* dense_seg_tok_off;   // [ceil(N / kDenseSegRows) + 1]
   int32_t* dense_n_segments;    // [1]
-  int32_t* dense_short_seg;     // [1] list 3 of that route: segment and first row of the short last
-  int32_t* dense_short_row0;    // [1] tile, if the batch's N leaves one
+  // 1 for the route of the shared parameters itself: row_src is the identity, every segment names
+  // slot 0 and tile t of list k starts at row t * tile_m[k], so a kernel that is given the batch's
+  // row count needs none of the arrays above (each lookup it skips is a dependent trip to L2, which
+  // is most of the duration of a launch over a few hundred rows).
+  int32_t identity;
   int32_t n_cu;                 // compute units of the pool's device (host side: sizes the persistent launches)
 };
 constexpr int kGemmSchedInts = 16 + 1024;
@@ -83,14 +83,10 @@ struct GemmArgs {
   int n_out, k;
   int n_rows;                         // rows of the whole batch (chooses between the kernels)
   int epi;
-  int n_mtiles_list[4];               // exact m-tile counts of the route's tile lists, computed on the host
+  int n_mtiles_list[2];               // exact m-tile counts of both tile lists, computed on the host
   int which_tiles;                    // set by the launcher: index into Route::tile_* ...
   int n_mtiles;                       // ... and that list's count
 };
-
-// m-tile counts of lists 2 and 3 for one segment of `rows` rows
-__host__ __device__ inline int tiles_over_128(int rows) { return (rows + 127) / 256; }
-__host__ __device__ inline int short_last_tile(int rows) { return rows % 256 > 0 && rows % 256 <= 128 ? 1 : 0; }
 
 void launch_gemm_bf16(const GemmArgs& g, const Route& rt, hipStream_t s);
 void launch_gemm_f32(const GemmArgs& g, const Route& rt, hipStream_t s);

@@ -103,7 +103,8 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) 
   __shared__ int seg_s[kMaxRequests + 1];
   const int lane = threadIdx.x & 63;
   const int srow = min(blockIdx.x * 4 + (int)(threadIdx.x >> 6), a.n_rows - 1);   // surplus wavefronts redo the last row
-  const size_t row = (size_t)rt.row_src[srow];
+  const bool ident = rt.identity != 0;               // shared parameters: identity row map, slot 0, no search
+  const size_t row = ident ? (size_t)srow : (size_t)rt.row_src[srow];
   constexpr int d = NV * 256;
   constexpr bool in_f32 = IN_F32 || !BF16;
   f32x4 v[NV];
@@ -117,15 +118,18 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) 
 #pragma unroll
     for (int i = 0; i < NV; ++i) *reinterpret_cast<f32x4*>(a.sum_out + row * d + i * 256 + lane * 4) = v[i];
   }
-  const int G = rt.n_segments[0];
-  for (int i = threadIdx.x; i <= G; i += 256) seg_s[i] = rt.seg_tok_off[i];
-  __syncthreads();
-  int lo = 0, hi = G;
-  while (hi - lo > 1) {
-    int mid = (lo + hi) >> 1;
-    if (seg_s[mid] <= srow) lo = mid; else hi = mid;
+  size_t slot_base = 0;
+  if (!ident) {
+    const int G = rt.n_segments[0];
+    for (int i = threadIdx.x; i <= G; i += 256) seg_s[i] = rt.seg_tok_off[i];
+    __syncthreads();
+    int lo = 0, hi = G;
+    while (hi - lo > 1) {
+      int mid = (lo + hi) >> 1;
+      if (seg_s[mid] <= srow) lo = mid; else hi = mid;
+    }
+    slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
   }
-  const size_t slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
   float s = 0.0f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];

@@ -167,7 +167,7 @@ struct hmi_pool {
   int32_t* d_head_meta = nullptr;      // [tenant] {n_classes, per_token}
   std::vector<uint8_t> head_loaded;
   std::vector<int32_t> last_distinct;  // tenants of the last routed batch
-  int last_n_mtiles[4] = {0, 0, 0, 0};  // its m-tile counts
+  int last_n_mtiles[2] = {0, 0};       // its m-tile counts
   int last_N = 0;                      // and rows
   float* w_scores = nullptr;           // [max_tokens, kHeadCols] raw scores
 
@@ -507,19 +507,18 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   const size_t MT = (size_t)c.max_tokens;
   const size_t max_tiles0 = MT / p->tile_m[0] + Rm + 1;
   const size_t max_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + Rm + 1 : 0;
-  const size_t max_tiles2 = p->bf16 ? MT / 256 + Rm + 1 : 0, max_tiles3 = p->bf16 ? Rm + 1 : 0;
   size_t n_i32 = 3 * (size_t)Rm            // ids, lens, req_slot
                  + 3 * (size_t)Rm          // req_tenant, kv_slot, kv_pos
                  + Rm + (Rm + 1)           // perm, tok_off
                  + 2 * (size_t)Rm          // seg_tenant, seg_slot
                  + 2 * ((size_t)Rm + 1)    // seg_req_off, seg_tok_off
                  + MT                      // row_src
-                 + 2 * (max_tiles0 + max_tiles1 + max_tiles2 + max_tiles3) + 8   // tile lists + counters
+                 + 2 * (max_tiles0 + max_tiles1) + 4   // tile lists + counters
                  + kGemmSchedInts;
   const bool dense = composite;
   const size_t dense_segs = MT / kDenseSegRows + 2;
   const size_t dense_tiles0 = MT / p->tile_m[0] + 2, dense_tiles1 = p->tile_m[1] ? MT / p->tile_m[1] + 2 : 0;
-  if (dense) n_i32 += 2 * dense_segs + 1 + MT + 2 * (dense_tiles0 + dense_tiles1) + 4;
+  if (dense) n_i32 += 2 * dense_segs + 1 + MT + 2 * (dense_tiles0 + dense_tiles1);
   CREATE_TRY(hipMalloc(&p->d_idx, n_i32 * sizeof(int32_t)));
   CREATE_TRY(hipMemset(p->d_idx, 0, n_i32 * sizeof(int32_t)));
   int32_t* q = p->d_idx;
@@ -534,12 +533,7 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   rt.tile_seg[0] = take(max_tiles0); rt.tile_row0[0] = take(max_tiles0);
   rt.tile_seg[1] = max_tiles1 ? take(max_tiles1) : nullptr;
   rt.tile_row0[1] = max_tiles1 ? take(max_tiles1) : nullptr;
-  rt.tile_seg[2] = max_tiles2 ? take(max_tiles2) : nullptr;
-  rt.tile_row0[2] = max_tiles2 ? take(max_tiles2) : nullptr;
-  rt.tile_seg[3] = max_tiles3 ? take(max_tiles3) : nullptr;
-  rt.tile_row0[3] = max_tiles3 ? take(max_tiles3) : nullptr;
-  rt.n_segments = take(1);
-  for (int k = 0; k < 4; ++k) rt.n_tiles[k] = take(1);
+  rt.n_segments = take(1); rt.n_tiles[0] = take(1); rt.n_tiles[1] = take(1);
   rt.gemm_sched = take(kGemmSchedInts);
   rt.tile_m[0] = p->tile_m[0]; rt.tile_m[1] = p->tile_m[1];
   rt.key_bits = bits_for(c.max_tenants);
@@ -557,16 +551,10 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
     rd.tile_seg[0] = take(dense_tiles0); rd.tile_row0[0] = take(dense_tiles0);
     rd.tile_seg[1] = dense_tiles1 ? take(dense_tiles1) : nullptr;
     rd.tile_row0[1] = dense_tiles1 ? take(dense_tiles1) : nullptr;
-    // lists 2 and 3 of the dense route: its segments are multiples of 256 rows except the last, so the
-    // tiles of more than 128 rows are a prefix of list 0, and the one short tile is written by the router
-    rd.tile_seg[2] = rd.tile_seg[0]; rd.tile_row0[2] = rd.tile_row0[0];
-    rd.tile_seg[3] = take(1); rd.tile_row0[3] = take(1);
     rt.dense_seg_tok_off = rd.seg_tok_off;
     rt.dense_n_segments = rd.n_segments;
-    rt.dense_short_seg = rd.tile_seg[3];
-    rt.dense_short_row0 = rd.tile_row0[3];
     rd.dense_seg_tok_off = nullptr; rd.dense_n_segments = nullptr;
-    rd.dense_short_seg = nullptr; rd.dense_short_row0 = nullptr;
+    rd.identity = 1;
     std::vector<int32_t> h(MT);
     for (size_t i = 0; i < MT; ++i) h[i] = (int32_t)i;
     CREATE_TRY(hipMemcpy(rd.row_src, h.data(), MT * sizeof(int32_t), hipMemcpyHostToDevice));
@@ -761,7 +749,7 @@ int32_t hmi_head_forward(hmi_pool_t* p, const void* h, float* scores, int32_t* l
   g.pool = p->d_heads; g.slot_stride = p->head_stride;
   g.w_off = 0; g.b_off = (size_t)kHeadCols * c.d_model * p->esize;
   g.n_out = kHeadCols; g.k = c.d_model; g.n_rows = p->last_N; g.epi = EPI_BIAS;
-  for (int k = 0; k < 4; ++k) g.n_mtiles_list[k] = p->last_n_mtiles[k];
+  g.n_mtiles_list[0] = p->last_n_mtiles[0]; g.n_mtiles_list[1] = p->last_n_mtiles[1];
   g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
   if (p->bf16) launch_gemm_bf16(g, rh, p->compute); else launch_gemm_f32(g, rh, p->compute);
   HeadArgs a{};
@@ -897,12 +885,10 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
 
   // ---- residency of the first layer: hits first (so they cannot be chosen as victims)
   const uint64_t now = ++p->clock;
-  int n_mtiles[4] = {0, 0, 0, 0};
+  int n_mtiles[2] = {0, 0};
   for (int t : p->distinct) {
     n_mtiles[0] += (p->tok_count[t] + p->tile_m[0] - 1) / p->tile_m[0];
     if (p->tile_m[1]) n_mtiles[1] += (p->tok_count[t] + p->tile_m[1] - 1) / p->tile_m[1];
-    n_mtiles[2] += tiles_over_128(p->tok_count[t]);
-    n_mtiles[3] += short_last_tile(p->tok_count[t]);
     const int s = p->slot_of_tenant[t];
     if (s >= 0) p->slot_stamp[s] = now;
   }
@@ -972,7 +958,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
   HIP_TRY(p, hipEventRecord(p->idx_ev[bi], s));
   p->last_R = R;
   p->last_distinct.assign(p->distinct.begin(), p->distinct.end());   // within the reserved capacity
-  for (int k = 0; k < 4; ++k) p->last_n_mtiles[k] = n_mtiles[k];
+  p->last_n_mtiles[0] = n_mtiles[0]; p->last_n_mtiles[1] = n_mtiles[1];
   p->last_N = (int)N;
 
   const int d = c.d_model, f = c.d_ff;
@@ -1013,7 +999,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       g.pool = p->d_pool; g.slot_stride = p->slot_stride;
       g.w_off = lay + p->tl[tw].off; g.b_off = lay + p->tl[tb].off;
       g.n_out = n_out; g.k = k; g.n_rows = (int)N; g.epi = epi;
-      for (int i = 0; i < 4; ++i) g.n_mtiles_list[i] = n_mtiles[i];
+      g.n_mtiles_list[0] = n_mtiles[0]; g.n_mtiles_list[1] = n_mtiles[1];
       g.which_tiles = 0; g.n_mtiles = n_mtiles[0];
           ProfSpan ps(p, HMI_KERNEL_GEMM);
       if (p->bf16) launch_gemm_bf16(g, rt, s); else launch_gemm_f32(g, rt, s);
@@ -1039,11 +1025,6 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       g.n_out = n_out; g.k = k; g.n_rows = (int)N; g.epi = epi;
       g.n_mtiles_list[0] = (int)((N + p->tile_m[0] - 1) / p->tile_m[0]);
       g.n_mtiles_list[1] = p->tile_m[1] ? (int)((N + p->tile_m[1] - 1) / p->tile_m[1]) : 0;
-      {   // pseudo-segments of kDenseSegRows rows, the last one shorter
-        const int whole = (int)(N / kDenseSegRows), rest = (int)(N % kDenseSegRows);
-        g.n_mtiles_list[2] = whole * (kDenseSegRows / 256) + tiles_over_128(rest);
-        g.n_mtiles_list[3] = short_last_tile(rest);
-      }
       g.which_tiles = 0; g.n_mtiles = g.n_mtiles_list[0];
           ProfSpan ps(p, HMI_KERNEL_GEMM);
       if (p->bf16) launch_gemm_bf16(g, p->rt_dense, s); else launch_gemm_f32(g, p->rt_dense, s);

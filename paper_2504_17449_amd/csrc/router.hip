@@ -198,38 +198,6 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
     if (tid == 0) rt.n_tiles[h][0] = tile_carry;
   }
 
-  // ---- lists 2 and 3: 256-row tiles, a last tile of at most 128 rows kept apart
-  if (rt.tile_seg[2] && rt.tile_seg[3]) {
-    int big_carry = 0, short_carry = 0;
-    const int grounds = (G + kRouterThreads - 1) / kRouterThreads;
-    for (int c = 0; c < grounds; ++c) {
-      int g = c * kRouterThreads + tid;
-      int rows = g < G ? segtok_s[g + 1] - segtok_s[g] : 0;
-      int nb = tiles_over_128(rows), ns = short_last_tile(rows);
-      int tot_b, tot_s;
-      int base_b = block_exscan(nb, wave_tot, tot_b) + big_carry;
-      int base_s = block_exscan(ns, wave_tot, tot_s) + short_carry;
-      for (int t = 0; t < nb; ++t) {
-        rt.tile_seg[2][base_b + t] = g;
-        rt.tile_row0[2][base_b + t] = segtok_s[g] + t * 256;
-      }
-      if (ns) {
-        rt.tile_seg[3][base_s] = g;
-        rt.tile_row0[3][base_s] = segtok_s[g] + nb * 256;
-      }
-      big_carry += tot_b;
-      short_carry += tot_s;
-    }
-    if (tid == 0) { rt.n_tiles[2][0] = big_carry; rt.n_tiles[3][0] = short_carry; }
-  }
-  if (rt.dense_short_seg && tid == 0) {
-    // the dense route's segments are whole multiples of 256 rows except the last one
-    const int Gd = (N + kDenseSegRows - 1) / kDenseSegRows;
-    const int last_rows = N - (Gd - 1) * kDenseSegRows;
-    rt.dense_short_seg[0] = Gd - 1;
-    rt.dense_short_row0[0] = (Gd - 1) * kDenseSegRows + tiles_over_128(last_rows) * 256;
-  }
-
   // ---- sorted row -> original row, one wavefront per request
   for (int p = w; p < R; p += kWaves) {
     const int src0 = tok_s[perm[p]], dst0 = stok_s[p], len = stok_s[p + 1] - dst0;
