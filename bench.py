@@ -370,7 +370,8 @@ def main() -> int:
     elif wl.n_layers >= 6:
         parity_note = ("bf16, six chained layers: rel-Frobenius <= 1e-2 and every |error| <= 2e-2 + half a bf16 unit of the "
                        "reference value; the flat 2e-2 max-abs bar is met by two-layer stacks of the same block and missed "
-                       "by up to 3e-3 here at outputs of magnitude 4 and more, where rounding the result to bf16 alone costs 1.6e-2")
+                       "by up to 3e-3 here at outputs of magnitude 4 and more, where rounding the result to bf16 alone costs 1.6e-2; "
+                       "the fp32 result of the same stack (hmi_stack_forward_f32) meets both flat bars")
     else:
         parity_note = "bf16: max-abs <= 2e-2 and rel-Frobenius <= 1e-2 against the fp64 oracle"
     out = {

@@ -161,6 +161,17 @@ int32_t hmi_stack_forward(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_e
                           const void* x, void* y, const int32_t* tenant_ids,
                           const int32_t* seq_lens, int32_t n_requests);
 
+/* hmi_stack_forward with the result left unrounded: y is DEVICE float [N, d_model] whatever the
+ * pool's storage type (x stays in the storage type).  The stack carries its hidden states in fp32
+ * between layers; this call hands the last layer's fp32 result out instead of rounding it to bf16,
+ * for callers that go on computing in fp32 (an output head, a further stack) and for checking the
+ * arithmetic of a deep stack apart from the rounding of its result (half a bf16 unit is 0.0156 for
+ * values of magnitude 4 to 8).  Not available from pools that run the one-kernel adapter
+ * (HMI_ERR_ARG). */
+int32_t hmi_stack_forward_f32(hmi_pool_t* pool, int32_t layer_begin, int32_t layer_end,
+                              const void* x, float* y, const int32_t* tenant_ids,
+                              const int32_t* seq_lens, int32_t n_requests);
+
 /* Representation retrieval, GPU side (Sec. 3.3.1): the hidden states that enter the higher layers
  * are aggregated from precomputed representations of three-token fragments, one fragment centred
  * on every token.  table: DEVICE [n_entries, 3, d_model], pool dtype (row e holds the

@@ -22,7 +22,7 @@ HMI_F32, HMI_BF16 = 0, 1
 HMI_BLOCK_FFN, HMI_BLOCK_ENC_POSTLN, HMI_BLOCK_DEC_PRELN, HMI_BLOCK_ADAPTER, HMI_BLOCK_ENC_ADAPTER, HMI_BLOCK_DEC_ADAPTER = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ["hmi_pool_create", "hmi_pool_load_tenant", "hmi_pool_alias_tenant", "hmi_pool_load_shared", "hmi_pool_load_head", "hmi_head_forward",
-           "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_plot_aggregate", "hmi_layer_forward", "hmi_layer_forward_static", "hmi_stack_forward",
+           "hmi_kv_create", "hmi_prefill", "hmi_decode_step", "hmi_plot_aggregate", "hmi_layer_forward", "hmi_layer_forward_static", "hmi_stack_forward", "hmi_stack_forward_f32",
            "hmi_get_route",
            "hmi_pool_prefetch", "hmi_pool_stats", "hmi_pool_profile", "hmi_pool_profile_read", "hmi_pool_image_bytes", "hmi_last_error",
            "hmi_pool_destroy",
@@ -77,6 +77,8 @@ def _load() -> C.CDLL:
     lib.hmi_layer_forward_static.restype = i32
     lib.hmi_stack_forward.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
     lib.hmi_stack_forward.restype = i32
+    lib.hmi_stack_forward_f32.argtypes = [vp, i32, i32, vp, vp, pi32, pi32, i32]
+    lib.hmi_stack_forward_f32.restype = i32
     lib.hmi_get_route.argtypes = [vp, pi32, pi32, pi32, pi32, pi32]
     lib.hmi_get_route.restype = i32
     lib.hmi_pool_prefetch.argtypes = [vp, i32, pi32, i32]
@@ -222,6 +224,15 @@ def hmi_stack_forward(pool: int, layer_begin: int, layer_end: int, x_ptr: int, y
                                  ids.shape[0])
 
 
+def hmi_stack_forward_f32(pool: int, layer_begin: int, layer_end: int, x_ptr: int, y_ptr: int,
+                          tenant_ids, seq_lens) -> int:
+    ids, lens = _i32(tenant_ids), _i32(seq_lens)
+    if ids.shape != lens.shape or ids.ndim != 1:
+        raise ValueError("tenant_ids and seq_lens must be 1-D and of equal length")
+    return lib.hmi_stack_forward_f32(pool, layer_begin, layer_end, x_ptr, y_ptr, _p32(ids), _p32(lens),
+                                     ids.shape[0])
+
+
 def hmi_get_route(pool: int, max_requests: int):
     perm = np.zeros(max_requests, np.int32)
     seg_tenant = np.zeros(max_requests, np.int32)
@@ -360,6 +371,11 @@ class Pool:
     def stack_forward(self, layer_begin: int, layer_end: int, x, y, tenant_ids, seq_lens) -> None:
         self._check(hmi_stack_forward(self.h, layer_begin, layer_end, x.data_ptr(), y.data_ptr(),
                                       tenant_ids, seq_lens))
+
+    def stack_forward_f32(self, layer_begin: int, layer_end: int, x, y, tenant_ids, seq_lens) -> None:
+        """y: float32 tensor [N, d_model]; the last layer's result is not rounded to the storage type."""
+        self._check(hmi_stack_forward_f32(self.h, layer_begin, layer_end, x.data_ptr(), y.data_ptr(),
+                                          tenant_ids, seq_lens))
 
     def route(self) -> dict:
         rc, rt = hmi_get_route(self.h, self.max_requests)

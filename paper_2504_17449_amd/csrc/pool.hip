@@ -834,9 +834,11 @@ enum { KV_NONE = 0, KV_PREFILL = 1, KV_DECODE = 2 };
 // one row per request (seq_lens == nullptr), appends it to the line and attends over the line.
 static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
                             const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R, int kv,
-                            const int32_t* seq_slots) {
+                            const int32_t* seq_slots, bool y_f32 = false) {
   if (!p) return HMI_ERR_ARG;
   if (R == 0) return HMI_OK;
+  if (y_f32 && p->cfg.block == HMI_BLOCK_ADAPTER && p->adapter_fused)
+    return fail(p, HMI_ERR_ARG, "fp32 output is not available from the one-kernel adapter");
   if (kv == KV_DECODE && R > 0 && R <= p->cfg.max_requests) seq_lens = p->ones.data();
   if (R > p->cfg.max_requests) return fail(p, HMI_ERR_SHAPE, "%d requests > max_requests %d", R, p->cfg.max_requests);
   if (R < 0 || !x || !y || !tenant_ids || !seq_lens) return fail(p, HMI_ERR_ARG, "null pointer or negative request count");
@@ -970,6 +972,9 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
   const void* in_res = x;       // layer input as residual / LayerNorm operand
   bool in_res_f32 = f32;
 
+  // where the last layer's LayerNorm puts the result: y in the storage type, or y as fp32 on request
+  float* const y_out32 = y_f32 ? static_cast<float*>(y) : nullptr;
+  void* const y_outst = y_f32 ? nullptr : y;
   for (int layer = layer_begin; layer < layer_end; ++layer) {
     const bool last = layer + 1 == layer_end;
     // weights of this layer must have landed before the first kernel that reads them
@@ -1076,7 +1081,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
       case HMI_BLOCK_FFN:
         gemm(in_st, d, T_W1, T_B1, f, d, EPI_BIAS_GELU, p->w_hmid, f, nullptr, 0, false, false, nullptr);
         gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, p->w_z, d, in_res, d, in_res_f32, true, nullptr);
-        lnorm(p->w_z, true, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, T_LNG, T_LNB);
+        lnorm(p->w_z, true, last ? y_out32 : p->w_y32, last ? y_outst : (void*)p->w_yst, T_LNG, T_LNB);
         break;
       case HMI_BLOCK_ADAPTER:
         if (p->adapter_fused) {
@@ -1091,7 +1096,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
         }
         gemm(in_st, d, T_W1, T_B1, f, d, EPI_BIAS_RELU, p->w_hmid, f, nullptr, 0, false, false, nullptr);
         if (last)
-          gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, y, d, in_res, d, in_res_f32, f32, nullptr);
+          gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, y, d, in_res, d, in_res_f32, f32 || y_f32, nullptr);
         else
           gemm(p->w_hmid, f, T_W2, T_B2, d, f, EPI_BIAS_RESID, p->w_y32, d, in_res, d, in_res_f32, true, p->w_yst);
         break;
@@ -1103,7 +1108,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
         gemm(p->bf16 ? (const void*)p->w_act : (const void*)p->w_x1, d, A_W1, A_B1, f, d, EPI_BIAS_GELU,
              p->w_hmid, f, nullptr, 0, false, false, nullptr);
         gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_z, d, p->w_x1, d, true, true, nullptr);
-        lnorm(p->w_z, true, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, A_LN2G, A_LN2B);
+        lnorm(p->w_z, true, last ? y_out32 : p->w_y32, last ? y_outst : (void*)p->w_yst, A_LN2G, A_LN2B);
         break;
       case HMI_BLOCK_DEC_ADAPTER: {
         // the decoder-only counterpart: pre-LN, causal, residual stream carried in fp32
@@ -1114,7 +1119,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
         adapter_step();                                                     // w_act -> w_ctx
         slnorm(in_res, in_res_f32, p->w_ctx, nullptr, p->w_act, A_LN2G, A_LN2B, p->w_x1);   // x1 = x + a', LN2(x1)
         sgemm(p->w_act, d, A_W1, A_B1, f, d, EPI_BIAS_GELU, p->w_hmid, f, nullptr, 0, false, false);
-        if (last) sgemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, y, d, p->w_x1, d, true, f32);
+        if (last) sgemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, y, d, p->w_x1, d, true, f32 || y_f32);
         else sgemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_y32, d, p->w_x1, d, true, true);
         break;
       }
@@ -1129,7 +1134,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
         sgemm(p->bf16 ? (const void*)p->w_act : (const void*)p->w_x1, d, A_W1, A_B1, f, d, EPI_BIAS_GELU,
               p->w_hmid, f, nullptr, 0, false, false);
         sgemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_z, d, p->w_x1, d, true, true);
-        slnorm(p->w_z, true, nullptr, last ? nullptr : p->w_y32, last ? y : (void*)p->w_yst, A_LN2G, A_LN2B);
+        slnorm(p->w_z, true, nullptr, last ? y_out32 : p->w_y32, last ? y_outst : (void*)p->w_yst, A_LN2G, A_LN2B);
         break;
       }
       case HMI_BLOCK_DEC_PRELN:
@@ -1140,7 +1145,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
         lnorm(p->w_x1, true, nullptr, p->w_act, A_LN2G, A_LN2B);
         gemm(p->w_act, d, A_W1, A_B1, f, d, EPI_BIAS_GELU, p->w_hmid, f, nullptr, 0, false, false, nullptr);
         if (last)
-          gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, y, d, p->w_x1, d, true, f32, nullptr);
+          gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, y, d, p->w_x1, d, true, f32 || y_f32, nullptr);
         else
           gemm(p->w_hmid, f, A_W2, A_B2, d, f, EPI_BIAS_RESID, p->w_y32, d, p->w_x1, d, true, true, nullptr);
         break;
@@ -1160,6 +1165,11 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
 int32_t hmi_stack_forward(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, void* y,
                           const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
   return forward_impl(p, layer_begin, layer_end, x, y, tenant_ids, seq_lens, R, KV_NONE, nullptr);
+}
+
+int32_t hmi_stack_forward_f32(hmi_pool_t* p, int32_t layer_begin, int32_t layer_end, const void* x, float* y,
+                              const int32_t* tenant_ids, const int32_t* seq_lens, int32_t R) {
+  return forward_impl(p, layer_begin, layer_end, x, y, tenant_ids, seq_lens, R, KV_NONE, nullptr, true);
 }
 
 int32_t hmi_kv_create(hmi_pool_t* p, int32_t max_seqs, int32_t max_len) {

@@ -60,6 +60,12 @@ def run_full(wl, sample_kw=None, tenants=None, heads=False, deep_stack=False):
         torch.cuda.synchronize()
         check_route(pool, ids, lens)
         y_gpu = harness.device_to_f64(y)
+        y32_gpu = None
+        if deep_stack:      # the same stack with its fp32 result handed out unrounded
+            y32 = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+            pool.stack_forward_f32(0, wl.n_layers, x, y32, ids, lens)
+            torch.cuda.synchronize()
+            y32_gpu = y32.cpu().numpy().astype(np.float64)
         if heads:   # the tenants' output heads on the (seeded) input hidden states of the same batch
             from tests.test_gpu_parity import check_heads
             X64 = np.concatenate([synth.hidden_states(wl, r, int(lens[r])) for r in range(len(ids))]).astype(np.float64)
@@ -74,6 +80,15 @@ def run_full(wl, sample_kw=None, tenants=None, heads=False, deep_stack=False):
           f"rel_fro={rel:.3e} max|y_ref|={np.nanmax(np.abs(y_ref)):.2f}", flush=True)
     assert ok or (deep_stack and deep_stack_ok(y_gpu, y_ref, rows_of(lens, sample), max_abs, rel, ok, wl.name)), (max_abs, rel)
     assert np.isfinite(y_gpu).all()
+    if y32_gpu is not None:
+        # Without the rounding of the result the stack is held to both flat bars: what is left is the arithmetic.
+        m32, r32, ok32 = compare(y32_gpu, y_ref, rows_of(lens, sample), wl.dtype)
+        print(f"  fp32 result of the same stack: max_abs={m32:.3e} rel_fro={r32:.3e}", flush=True)
+        assert ok32, (m32, r32)
+        # and the bf16 result is that fp32 result rounded once
+        rows = rows_of(lens, sample)
+        y32_as_bf16 = torch.from_numpy(y32_gpu[rows]).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+        assert np.array_equal(y32_as_bf16, y_gpu[rows])
 
 
 def test_hbert_two_encoder_layers_1000_tenants_full_size():
@@ -515,6 +530,12 @@ def test_adapter_kernel_at_the_request_limit_more_units_than_a_workgroup_lists()
         torch.cuda.synchronize()
         check_route(pool, ids, lens)
         y_gpu = harness.device_to_f64(y)
+        y32_gpu = None
+        if deep_stack:      # the same stack with its fp32 result handed out unrounded
+            y32 = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+            pool.stack_forward_f32(0, wl.n_layers, x, y32, ids, lens)
+            torch.cuda.synchronize()
+            y32_gpu = y32.cpu().numpy().astype(np.float64)
     finally:
         pool.close()
     sample = pick_sample(ids, lens, n_multi=6, n_single=8) + [0, len(ids) - 1]
