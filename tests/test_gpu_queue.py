@@ -139,3 +139,55 @@ def test_queue_forms_batches_runs_them_in_order_and_prefetches_the_next(hmi):
         if q is not None:
             q.close()
         pool.close()
+
+
+def test_queue_output_is_the_stack_call_on_the_gathered_batch_bit_for_bit(hmi):
+    """A pool without host tier (nothing to prefetch), two layers, requests scattered over separate device buffers:
+    what a request fetches from the queue is bit for bit what hmi_stack_forward writes for it when the same batch is
+    handed over as one packed tensor; batches close on the token limit."""
+    from paper_2504_17449_amd import harness
+    max_req, max_tok = 16, 300
+    wl = synth.Workload(name="queue_resident", block=synth.BLOCK_FFN, dtype="bf16", d_model=256, d_ff=512, n_heads=0,
+                        n_layers=2, n_tenants=6, n_requests=40, seq_min=3, seq_max=90, popularity="uniform", zipf_s=0.0,
+                        ln_eps=1e-12, hbm_slots=6, host_tier=False, seed=5)
+    ids, lens = synth.batch_ids_lens(wl)
+    reqs = [(int(t), int(n)) for t, n in zip(ids, lens)]
+    want_batches = form_batches(reqs, max_req, max_tok, wl.hbm_slots)
+    assert len(want_batches) >= 4 and all(len(b) < max_req for b in want_batches)       # the token limit closes them
+    pool = harness.create_pool(wl, max_requests=max_req, max_tokens=max_tok)
+    q = None
+    try:
+        harness.load_tenants(pool, wl)
+        q = hmi.Queue(pool, max_req, max_tok, max_waiting_batches=len(want_batches))
+        xs = [harness.host_to_device(synth.hidden_states(wl, r, n), "bf16") for r, (_, n) in enumerate(reqs)]
+        ys = [torch.zeros_like(x) for x in xs]
+        tickets = [q.push(t, xs[i]) for i, (t, _) in enumerate(reqs)]
+        assert None not in tickets and q.waiting() == len(want_batches)
+        for b, members in enumerate(want_batches):
+            assert q.run() == (b, len(members))
+            for i in members:
+                q.fetch(tickets[i], ys[i])
+        torch.cuda.synchronize()
+        for members in want_batches:
+            xb = torch.cat([xs[i] for i in members])
+            yb = torch.empty_like(xb)
+            pool.stack_forward(0, wl.n_layers, xb, yb, np.array([reqs[i][0] for i in members], np.int32),
+                               np.array([reqs[i][1] for i in members], np.int32))
+            torch.cuda.synchronize()
+            off = 0
+            for i in members:
+                n = reqs[i][1]
+                assert torch.equal(ys[i].view(torch.int16), yb[off:off + n].view(torch.int16)), i
+                off += n
+        # and against the oracle, every request
+        wofs = [weights_of(wl, l) for l in range(wl.n_layers)]
+        for i, (t, n) in enumerate(reqs):
+            h = synth.hidden_states(wl, i, n).astype(np.float64)
+            for l in range(wl.n_layers):
+                h = O.block_forward(wl.block, h, wofs[l](t), wl.n_heads, wl.ln_eps)
+            max_abs, rel, ok = compare(harness.device_to_f64(ys[i]), h, np.arange(n), "bf16")
+            assert ok, (i, t, n, max_abs, rel)
+    finally:
+        if q is not None:
+            q.close()
+        pool.close()
