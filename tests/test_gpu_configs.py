@@ -551,32 +551,49 @@ def test_adapter_kernel_at_the_request_limit_more_units_than_a_workgroup_lists()
 
 def test_ten_thousand_tenants_adapters_behind_the_host_tier_full_size():
     """bench.py --workload hbert_shared_adapter_10k as it is timed: all 10 000 tenants' six-layer adapters in pinned
-    host memory, 2 000 HBM slots, two consecutive Zipf batches of 1 024 ragged requests with the second one's tenants
-    prefetched during the first; sampled requests of both batches against the oracle, routing bit-exact."""
+    host memory, 2 000 HBM slots, two consecutive Zipf batches of 1 024 ragged requests pushed request by request into
+    the library's queue, the second batch's tenants prefetched while the first computes; sampled requests of both
+    batches against the oracle, routing bit-exact."""
+    import paper_2504_17449_amd as hmi
     from paper_2504_17449_amd import harness
     wl = synth.WORKLOADS["hbert_shared_adapter_10k"]
     t0 = time.time()
-    pool = harness.create_pool(wl, max_tokens=wl.n_requests * wl.seq_max)
+    max_tok = wl.n_requests * wl.seq_max
+    pool = harness.create_pool(wl, max_tokens=max_tok)
+    q = None
     try:
         harness.load_tenants(pool, wl, workers=16)
         print(f"{wl.name}: {wl.n_tenants} tenants x {wl.n_layers} layers in pinned memory, {time.time() - t0:.1f}s", flush=True)
+        q = hmi.Queue(pool, wl.n_requests, max_tok, max_waiting_batches=2)
         batches = [synth.batch_ids_lens(wl, b) for b in range(2)]
-        outs = []
+        outs, tickets = [], []
         for b in range(2):
             ids, lens, x = harness.batch_to_device(wl, b)
-            y = torch.empty_like(x)
-            pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
-            if b == 0:
-                for layer in range(wl.n_layers):
-                    pool.prefetch(layer, np.unique(batches[1][0]))
-            outs.append((ids, lens, y))
+            off = np.concatenate([[0], np.cumsum(lens)])
+            tk = [q.push(int(ids[r]), x[off[r]:off[r + 1]]) for r in range(len(ids))]
+            assert None not in tk and all(t >> 20 == b for t in tk)      # a batch is full at 1 024 requests: batch b exactly
+            tickets.append(tk)
+            outs.append((ids, lens, x, torch.empty_like(x)))
+        assert q.waiting() == 2
+        assert q.run() == (0, wl.n_requests)          # batch 1's tenants are prefetched behind it
+        st_mid = pool.stats()
+        assert q.run() == (1, wl.n_requests)
+        for b in range(2):
+            ids, lens, _, y = outs[b]
+            off = np.concatenate([[0], np.cumsum(lens)])
+            for r in range(len(ids)):
+                q.fetch(tickets[b][r], y[off[r]:off[r + 1]])
         torch.cuda.synchronize()
         check_route(pool, batches[1][0], batches[1][1])
         st = pool.stats()
         print(f"  stats {st}", flush=True)
         assert st["misses"] > 100 and st["evictions"] > 0
-        got = [harness.device_to_f64(y) for _, _, y in outs]
+        assert st["misses"] == st_mid["misses"]       # every tenant of batch 1 was resident when its forward started
+        got = [harness.device_to_f64(y) for _, _, _, y in outs]
+        outs = [(ids, lens, y) for ids, lens, _, y in outs]
     finally:
+        if q is not None:
+            q.close()
         pool.close()
     for b, ((ids, lens, _), y) in enumerate(zip(outs, got)):
         sample = pick_sample(ids, lens, n_multi=3, n_single=5)
