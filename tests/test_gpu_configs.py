@@ -530,12 +530,6 @@ def test_adapter_kernel_at_the_request_limit_more_units_than_a_workgroup_lists()
         torch.cuda.synchronize()
         check_route(pool, ids, lens)
         y_gpu = harness.device_to_f64(y)
-        y32_gpu = None
-        if deep_stack:      # the same stack with its fp32 result handed out unrounded
-            y32 = torch.empty(x.shape, dtype=torch.float32, device=x.device)
-            pool.stack_forward_f32(0, wl.n_layers, x, y32, ids, lens)
-            torch.cuda.synchronize()
-            y32_gpu = y32.cpu().numpy().astype(np.float64)
     finally:
         pool.close()
     sample = pick_sample(ids, lens, n_multi=6, n_single=8) + [0, len(ids) - 1]
