@@ -14,8 +14,9 @@
 //     MFMA; about four other instructions fit behind each one.
 //   * LDS reads run at 256 B/clk, fragment traffic is not a bound for 64 x 128 wavefront tiles.
 // Hence
-//   * 256 x 256 tiles (8 wavefronts x 128 accumulator registers): the fewest operand bytes
-//     per FLOP the register file allows;
+//   * 256 x 256 tiles: the fewest operand bytes per FLOP the register file allows, held either by
+//     8 wavefronts x 128 accumulator registers (two wavefronts per SIMD) or by 4 wavefronts x 256
+//     accumulators in the AGPR half of a 512-register budget (one per SIMD); see Geo below;
 //   * k-stages of 64 bf16 = 128 bytes per row: the eight lanes that copy a row fetch one
 //     whole cache line, every operand request is a full line;
 //   * all 160 KB of LDS are a ring of 2 activation and 3 weight stages of 32 KB; weight
@@ -45,15 +46,25 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kXcds = 8;
-constexpr int BM = 256, BN = 256, BK = 64, NW = 8, NTH = 64 * NW;
-constexpr int WTM = 64, WTN = 128, TM = 2, TN = 4;          // wavefront tile (4 x 2 wavefronts), MFMA tiles
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int WTN = 128, TN = 4;                             // a wavefront's 128 columns: four MFMA tiles
+// The workgroup is NW = 8 or 4 wavefronts, NW/2 x 2 over the tile: wavefront tiles of 64 x 128 (two per SIMD,
+// 128 accumulator registers each) or 128 x 128 (one per SIMD with 256 accumulators in the AGPR half of a
+// 512-register budget: a third less fragment traffic per MFMA and one instruction stream per matrix pipe,
+// but nothing to run while that one wavefront waits, so it pays only where the main loop is long).
+template <int NW>
+struct Geo {
+  static constexpr int NTH = 64 * NW;
+  static constexpr int WTM = BM / (NW / 2), TM = WTM / 32;  // wavefront tile rows, MFMA tiles
+  static constexpr int RH = WTM / 64;                       // output-row ids a lane keeps per tile
+  static constexpr int LD = BM / 8 / NW;                    // one-KB copies (8 rows x 128 B) per wavefront, operand and stage: 4 or 8
+  static constexpr int WAVE_SLICE = LD * 1024;              // the part of a stage slot that one wavefront's copies fill
+};
 constexpr int ROW_BYTES = BK * 2;                            // 128: one cache line per row and stage
 constexpr int A_STAGES = 2, W_STAGES = 3;
 constexpr int STAGE_BYTES = BM * ROW_BYTES;                  // 32 KB, same for both operands
 constexpr int W_RING = A_STAGES * STAGE_BYTES;               // byte offset of the weight ring
 constexpr int LDS_BYTES = W_RING + W_STAGES * STAGE_BYTES;   // 163840 = all of it
-constexpr int LD = BM / 8 / NW;                              // 4 one-KB copies (8 rows x 128 B) per wavefront, operand and stage
-constexpr int WAVE_SLICE = LD * 1024;                        // the 4 KB of a stage slot that one wavefront's copies fill
 
 __device__ __forceinline__ float bf2f(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
@@ -97,15 +108,18 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 // What a lane needs to know about a tile: where its copies come from and where the bias is.
+template <int NW>
 struct TileRegs {
   int n0, row0, rows;
   const char* Wb;                  // first weight row of the tile: tenant's matrix + n0 rows
   const uint16_t* bias;
-  uint32_t a_off[LD];              // byte offsets of this lane's activation copy sources at k = 0, plus 3072 - 1024 j
-  int out_row;                     // where row (wavefront's first row + lane) of the tile goes in C (row clamped to the tile)
+  uint32_t a_off[Geo<NW>::LD];     // byte offsets of this lane's activation copy sources at k = 0, plus 3072 - 1024 j
+  int out_row[Geo<NW>::RH];        // where row (wavefront's first row + 64 h + lane) of the tile goes in C (row clamped to the tile)
 };
 
-__device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, int w, int wave, int lane, TileRegs& tr) {
+template <int NW>
+__device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, int w, int wave, int lane, TileRegs<NW>& tr) {
+  constexpr int WTM = Geo<NW>::WTM, RH = Geo<NW>::RH, LD = Geo<NW>::LD;
   // Tile order: segment by segment; inside a segment n-tile by n-tile with the segment's
   // m-tiles innermost, so that the tiles which share a weight panel (and the few that
   // share an activation panel) run next to each other and the panel is fetched from HBM once.
@@ -122,14 +136,15 @@ __device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, in
   const size_t slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
   tr.Wb = g.pool + slot_base + g.w_off + (size_t)tr.n0 * (size_t)(g.k * 2);
   tr.bias = reinterpret_cast<const uint16_t*>(g.pool + slot_base + g.b_off);
-  tr.out_row = rt.row_src[tr.row0 + min((wave >> 1) * WTM + lane, tr.rows - 1)];
+#pragma unroll
+  for (int h = 0; h < RH; ++h) tr.out_row[h] = rt.row_src[tr.row0 + min((wave >> 1) * WTM + h * 64 + lane, tr.rows - 1)];
   // lane l fills LDS position (row l/8, chunk l%8) of an 8-row block with the global chunk
   // position ^ swizzle(row): the eight lanes of a row cover its whole 128-byte line.
 #pragma unroll
   for (int j = 0; j < LD; ++j) {
     const int row = (wave * LD + j) * 8 + (lane >> 3);
     const int src = rt.row_src[tr.row0 + min(row, tr.rows - 1)];
-    tr.a_off[j] = (uint32_t)src * (uint32_t)(g.lda * 2) + (((lane & 7) ^ swz_a(row)) << 4) + (3072 - j * 1024);
+    tr.a_off[j] = (uint32_t)src * (uint32_t)(g.lda * 2) + (((lane & 7) ^ swz_a(row)) << 4) + (3072 - (j & 3) * 1024);
   }
 }
 
@@ -145,10 +160,11 @@ __device__ __forceinline__ void finish_workgroup(const Route& rt, int xcd, int n
   }
 }
 
-template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
-__global__ __launch_bounds__(NTH) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int NW, int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4)))
 void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int WTM = Geo<NW>::WTM, TM = Geo<NW>::TM, LD = Geo<NW>::LD, WAVE_SLICE = Geo<NW>::WAVE_SLICE;
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -177,7 +193,7 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   if (claimer) claimed = atomicAdd(claim_ctr, 1);
   int budget = per_xcd;           // no workgroup can own more tiles than its XCD has: bounds the loop whatever the claims say
 
-  TileRegs cur, nxt;
+  TileRegs<NW> cur, nxt;
   load_tile(g, rt, w, wave, lane, cur);
   load_tile(g, rt, w_next < w_end ? w_next : w, wave, lane, nxt);
 
@@ -186,7 +202,7 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
 #pragma unroll
   for (int j = 0; j < LD; ++j) {
     const int row = (wave * LD + j) * 8 + (lane >> 3);
-    b_off[j] = (uint32_t)row * (uint32_t)(g.k * 2) + (((lane & 7) ^ swz_w(row)) << 4) + (3072 - j * 1024);
+    b_off[j] = (uint32_t)row * (uint32_t)(g.k * 2) + (((lane & 7) ^ swz_w(row)) << 4) + (3072 - (j & 3) * 1024);
   }
 
   // ---- fragment read offsets inside a stage slot for the four k-steps of a stage
@@ -206,19 +222,21 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   // of its own first stages that nobody consumes).  Needs KT >= 3, so that the copies
   // never reach the tile after next.
   int a_rd = 0, w_rd = 0;
-  // The four 1 KB copies of a wavefront's slice share one LDS base (one M0 write); the
+  // Four 1 KB copies of a wavefront's slice (all of it, or half) share one LDS base (one M0 write); the
   // instruction offset j KB that separates them applies to the global address too, so
   // the lane offsets carry 3072 - j KB and the uniform base pointer -3072.
 #define HMI_COPY4(SRC, VOFF, SLOT_OFF)                                                            \
   {                                                                                               \
     const char* src_ = (SRC) - 3072;                                                              \
-    lds_ptr_t dst_ = (lds_ptr_t)(smem + (SLOT_OFF) + wave * WAVE_SLICE);                          \
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[0]), dst_, 16, 0, 0);              \
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[1]), dst_, 16, 1024, 0);           \
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[2]), dst_, 16, 2048, 0);           \
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[3]), dst_, 16, 3072, 0);           \
+    _Pragma("unroll") for (int q_ = 0; q_ < LD / 4; ++q_) {                                       \
+      lds_ptr_t dst_ = (lds_ptr_t)(smem + (SLOT_OFF) + wave * WAVE_SLICE + q_ * 4096);            \
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[4 * q_ + 0]), dst_, 16, 0, 0);    \
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[4 * q_ + 1]), dst_, 16, 1024, 0); \
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[4 * q_ + 2]), dst_, 16, 2048, 0); \
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(src_ + (VOFF)[4 * q_ + 3]), dst_, 16, 3072, 0); \
+    }                                                                                             \
   }
-  static_assert(LD == 4, "HMI_COPY4 issues four copies");
+  static_assert(LD % 4 == 0, "HMI_COPY4 issues the copies in groups of four");
 
   bf16x8 fx[2][TM], fw[2][TN];
   f32x16 acc[TM][TN];
@@ -340,7 +358,7 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
     }
 
     // ================= epilogue of the current tile =================
-    // Staging patch of this wavefront: its own 4 KB slice of the two slots that stage KT-1
+    // Staging patch of this wavefront: the first 4 KB of its own slice of the two slots that stage KT-1
     // occupied.  A row keeps its 16-byte chunk c at chunk position c ^ (row & 15).
     // Rows past the end of a short tile are replaced by the tile's last row of the same
     // 32-row block (same data to the same address: harmless), which keeps the code free
@@ -361,11 +379,17 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
       for (int i = 0; i < TM; ++i) {
         const int mbase = wm * WTM + i * 32;
         if (mbase < cur.rows) {
+          if (NW == 4) {   // the row blocks still to come stay where the MFMAs left them (the AGPR half) until their turn
+#pragma unroll
+            for (int i2 = i + 1; i2 < TM; ++i2)
+#pragma unroll
+              for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i2][j]));
+          }
           const int rmax = min(31, cur.rows - 1 - mbase);     // last valid row of this 32-row block
           unsigned char* wrow = ((l32 & 16) ? patch1 : patch0) + (l32 & 15) * 256;
           uint32_t orow[8];                                   // row of C for each of this lane's 8 pieces
 #pragma unroll
-          for (int it = 0; it < 8; ++it) orow[it] = (uint32_t)__shfl(cur.out_row, i * 32 + min(it * 4 + (lane >> 4), rmax), 64);
+          for (int it = 0; it < 8; ++it) orow[it] = (uint32_t)__shfl(cur.out_row[i >> 1], (i & 1) * 32 + min(it * 4 + (lane >> 4), rmax), 64);
 #pragma unroll
           for (int pass = 0; pass < PASSES; ++pass) {
             const int col = cur.n0 + wn * WTN + pass * 64 + c * COLS_PER_CHUNK;
@@ -462,34 +486,39 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   finish_workgroup(rt, xcd, n_local);
 }
 
-template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
+template <int NW, int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
 void launch_one(const GemmArgs& g, const Route& rt, hipStream_t s) {
-  auto kern = gemm_bf16_p256_kernel<EPI, OUT_F32, RESID_F32, HAS_C2>;
+  auto kern = gemm_bf16_p256_kernel<NW, EPI, OUT_F32, RESID_F32, HAS_C2>;
   const int n_cu = rt.n_cu >= kXcds ? rt.n_cu : 256;
   const int nt_n = g.n_out / BN;
   const long long total = (long long)g.n_mtiles * nt_n;
   if (total <= 0) return;
   const int per_xcd = (int)((total + kXcds - 1) / kXcds);
   const int local = per_xcd < n_cu / kXcds ? per_xcd : n_cu / kXcds;   // workgroups per XCD: at most one per compute unit
-  hipLaunchKernelGGL(kern, dim3(local * kXcds), dim3(NTH), LDS_BYTES, s, g, rt, (int)total, per_xcd);
+  hipLaunchKernelGGL(kern, dim3(local * kXcds), dim3(Geo<NW>::NTH), LDS_BYTES, s, g, rt, (int)total, per_xcd);
 }
 
-template <int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
+template <int NW, int EPI, bool OUT_F32, bool RESID_F32, bool HAS_C2>
 void allow_lds() {
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_p256_kernel<EPI, OUT_F32, RESID_F32, HAS_C2>),
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_p256_kernel<NW, EPI, OUT_F32, RESID_F32, HAS_C2>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
 }
 
+// Which geometry a launch gets (measured on the FFN and encoder workloads): launches that add a residual (output
+// projection, second FFN GEMM) run with four wavefronts, 3-6 % faster there (no spills in their fp32 epilogue, a
+// long main loop in the second FFN GEMM); bias-only and activation launches keep eight, whose two wavefronts per
+// SIMD overlap each other's epilogue latencies (the first FFN GEMM is 11 % slower with four).
+constexpr int kWavesPlain = 8, kWavesResid = 4;
 }  // namespace
 
 // every instantiation launch_gemm_bf16_p256 can pick
 void init_gemm_bf16_p256_kernels() {
-  allow_lds<EPI_BIAS, false, false, true>();   allow_lds<EPI_BIAS, false, false, false>();
-  allow_lds<EPI_BIAS_GELU, false, false, false>();
-  allow_lds<EPI_BIAS_RELU, false, false, false>();
-  allow_lds<EPI_BIAS_RESID, true, true, true>();   allow_lds<EPI_BIAS_RESID, true, true, false>();
-  allow_lds<EPI_BIAS_RESID, true, false, true>();  allow_lds<EPI_BIAS_RESID, true, false, false>();
-  allow_lds<EPI_BIAS_RESID, false, true, false>(); allow_lds<EPI_BIAS_RESID, false, false, false>();
+  allow_lds<kWavesPlain, EPI_BIAS, false, false, true>();   allow_lds<kWavesPlain, EPI_BIAS, false, false, false>();
+  allow_lds<kWavesPlain, EPI_BIAS_GELU, false, false, false>();
+  allow_lds<kWavesPlain, EPI_BIAS_RELU, false, false, false>();
+  allow_lds<kWavesResid, EPI_BIAS_RESID, true, true, true>();   allow_lds<kWavesResid, EPI_BIAS_RESID, true, true, false>();
+  allow_lds<kWavesResid, EPI_BIAS_RESID, true, false, true>();  allow_lds<kWavesResid, EPI_BIAS_RESID, true, false, false>();
+  allow_lds<kWavesResid, EPI_BIAS_RESID, false, true, false>(); allow_lds<kWavesResid, EPI_BIAS_RESID, false, false, false>();
 }
 
 // Preconditions (checked by the caller): n_out % 256 == 0, k % 64 == 0, k >= 192,
@@ -499,18 +528,18 @@ void launch_gemm_bf16_p256(const GemmArgs& g, const Route& rt, hipStream_t s) {
   const bool c2 = g.C2 != nullptr;
   switch (g.epi) {
     case EPI_BIAS:
-      return c2 ? launch_one<EPI_BIAS, false, false, true>(g, rt, s) : launch_one<EPI_BIAS, false, false, false>(g, rt, s);
+      return c2 ? launch_one<kWavesPlain, EPI_BIAS, false, false, true>(g, rt, s) : launch_one<kWavesPlain, EPI_BIAS, false, false, false>(g, rt, s);
     case EPI_BIAS_GELU:
-      return launch_one<EPI_BIAS_GELU, false, false, false>(g, rt, s);
+      return launch_one<kWavesPlain, EPI_BIAS_GELU, false, false, false>(g, rt, s);
     case EPI_BIAS_RELU:
-      return launch_one<EPI_BIAS_RELU, false, false, false>(g, rt, s);
+      return launch_one<kWavesPlain, EPI_BIAS_RELU, false, false, false>(g, rt, s);
     default:
       if (g.out_f32) {
-        if (g.resid_f32) return c2 ? launch_one<EPI_BIAS_RESID, true, true, true>(g, rt, s) : launch_one<EPI_BIAS_RESID, true, true, false>(g, rt, s);
-        return c2 ? launch_one<EPI_BIAS_RESID, true, false, true>(g, rt, s) : launch_one<EPI_BIAS_RESID, true, false, false>(g, rt, s);
+        if (g.resid_f32) return c2 ? launch_one<kWavesResid, EPI_BIAS_RESID, true, true, true>(g, rt, s) : launch_one<kWavesResid, EPI_BIAS_RESID, true, true, false>(g, rt, s);
+        return c2 ? launch_one<kWavesResid, EPI_BIAS_RESID, true, false, true>(g, rt, s) : launch_one<kWavesResid, EPI_BIAS_RESID, true, false, false>(g, rt, s);
       }
-      if (g.resid_f32) return launch_one<EPI_BIAS_RESID, false, true, false>(g, rt, s);
-      return launch_one<EPI_BIAS_RESID, false, false, false>(g, rt, s);
+      if (g.resid_f32) return launch_one<kWavesResid, EPI_BIAS_RESID, false, true, false>(g, rt, s);
+      return launch_one<kWavesResid, EPI_BIAS_RESID, false, false, false>(g, rt, s);
   }
 }
 
