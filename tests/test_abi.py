@@ -38,6 +38,18 @@ def test_argument_errors_need_no_gpu():
     rc, h = pkg.hmi_pool_create(block=0, dtype=1, d_model=100, d_ff=64, max_tenants=1,
                                 max_requests=1, max_tokens=1)
     assert rc == pkg.HMI_ERR_ARG and "multiples" in pkg.hmi_last_error(None)
+    # the other entry points with no pool: an error code, nothing touched, no GPU call
+    for name in ("hmi_stack_forward", "hmi_stack_forward_f32"):
+        assert getattr(pkg.lib, name)(None, 0, 1, None, None, None, None, 0) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_layer_forward_static(None, 0, None, None, None, None, 0) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_pool_alias_tenant(None, 0, 0) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_pool_prefetch(None, 0, None, 0) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_queue_create(None, 1, 1, 1, None) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_queue_push(None, 0, 1, None, None) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_queue_run(None, None, None) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_queue_fetch(None, 0, None) == pkg.HMI_ERR_ARG
+    assert pkg.lib.hmi_queue_waiting(None) == 0
+    assert pkg.lib.hmi_queue_destroy(None) == pkg.HMI_OK
 
 
 def test_bench_refuses_more_than_one_gpu():

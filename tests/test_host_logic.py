@@ -1,8 +1,7 @@
-"""Host-side pieces that need no GPU: bench.py's contract at the command line, where its roofline.traffic comes from,
-and the workload table against the configurations the target names."""
+"""Host-side pieces that need no GPU: where bench.py's roofline.traffic comes from, the workload table against the
+configurations the target names, tenants that share a weight set."""
 import os
 import re
-import subprocess
 import sys
 
 import numpy as np
@@ -10,12 +9,6 @@ import numpy as np
 import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-
-
-def test_bench_refuses_more_than_one_gpu_with_a_message():
-    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
-    assert r.returncode != 0
-    assert "one GPU" in r.stderr and r.stdout.strip() == ""
 
 
 def test_roofline_traffic_is_read_from_the_committed_counter_summary():
