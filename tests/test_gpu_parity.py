@@ -41,6 +41,13 @@ def run_case(hmi, wl, sample=None, batch=0, tenants="touched", slack=0):
         torch.cuda.synchronize()
         check_route(pool, ids, lens)
         y_gpu = harness.device_to_f64(cur)
+        if wl.n_layers > 1:
+            # the same stack with its result handed out as fp32: rounded once to the storage type it is y, bit for bit
+            y32 = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+            pool.stack_forward_f32(0, wl.n_layers, x, y32, ids, lens)
+            torch.cuda.synchronize()
+            assert torch.equal(y32.to(cur.dtype).view(torch.int16 if wl.dtype == "bf16" else torch.int32),
+                               cur.view(torch.int16 if wl.dtype == "bf16" else torch.int32))
     finally:
         pool.close()
     reqs = list(range(len(ids))) if sample is None else list(sample)
