@@ -154,6 +154,23 @@ def test_bf16_adapter_rank_64(hmi):
     run_case(hmi, small(synth.BLOCK_ADAPTER, "bf16", d_model=768, d_ff=64, seq_max=128, seq_min=128))
 
 
+def test_one_kernel_adapter_refuses_the_fp32_result_call(hmi):
+    """The one-kernel adapter rounds as it stores: asking it for an fp32 result is an argument error, y untouched."""
+    from paper_2504_17449_amd import harness
+    wl = small(synth.BLOCK_ADAPTER, "bf16", d_model=256, d_ff=64, n_requests=3, seq_max=20)
+    ids, lens, x = harness.batch_to_device(wl)
+    pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl)
+        y32 = torch.full(x.shape, 7.0, dtype=torch.float32, device=x.device)
+        assert hmi.hmi_stack_forward_f32(pool.h, 0, 1, x.data_ptr(), y32.data_ptr(), ids, lens) == hmi.HMI_ERR_ARG
+        assert "fp32" in hmi.hmi_last_error(pool.h)
+        torch.cuda.synchronize()
+        assert bool((y32 == 7.0).all())
+    finally:
+        pool.close()
+
+
 @pytest.mark.parametrize("d_model", [256, 512, 768])
 def test_fused_adapter_ragged_large_weights(hmi, d_model):
     """Single-layer bf16 adapter pools with rank 64 run the one-kernel path (rows through LDS,
