@@ -4,7 +4,7 @@
 // is cut into many small independent items that keep every compute unit's memory pipe full:
 //
 //   item = (32 rows of one segment) x (32 output columns) x (all of k), one WAVEFRONT per item,
-//   five items per workgroup, no workgroup barriers.
+//   five items per workgroup (three in small launches, see Ring), no workgroup barriers.
 //
 // A launch with so few items that they would not even give every compute unit one workgroup (a decode
 // step through parameters that all tenants share: a few hundred rows in all) is bound by the latency of
@@ -12,7 +12,7 @@
 // a quarter of k each and add their partial sums through LDS in a fixed order.
 //
 // A wavefront streams its 32 weight rows and its 32 activation rows (gathered through row_src) through a
-// private LDS ring of four stages of 64 k (direct-to-LDS copies of full 128-byte lines, three stages in
+// private LDS ring of four to six stages of 64 k (direct-to-LDS copies of full 128-byte lines, all but one stage in
 // flight), reads the weights back as MFMA first operands in the permuted row order that gives a lane 16
 // consecutive output columns of one row, and the activations as second operands.  Items of the four row
 // blocks of one 128-row tile are neighbours, so a weight panel that several row blocks need is fetched
@@ -34,11 +34,25 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 constexpr int SK = 32;                    // rows and columns of an item
-constexpr int STAGES = 4, STAGE_BYTES = SK * 128;          // per operand: 32 rows of 64 k
-constexpr int X_RING = STAGES * STAGE_BYTES;               // a wavefront's ring: weight stages, then activation stages
-constexpr int WAVE_LDS = 2 * STAGES * STAGE_BYTES;
-constexpr int WAVES = 5, LDS_BYTES = WAVES * WAVE_LDS;     // 160 KB
+constexpr int STAGE_BYTES = SK * 128;                      // per operand: 32 rows of 64 k
 constexpr int KSPLIT = 4;                                  // wavefronts that share the k of one item in the split variant
+// Ring depth and wavefronts per workgroup (always 160 KB of LDS, or all the split variant can use):
+//   4 stages x 5 wavefronts: launches with many items (per-tenant decode steps), bound by streaming the weights;
+//   6 stages x 3 wavefronts, 5 stages in the split variant: launches with at most kDeepMaxItems items (shared layers,
+//   a few hundred rows): there a launch lasts as long as one wavefront's walk over k, a chain of
+//   k / 64 / (stages in flight) round trips to L2 or beyond, so more stages in flight shorten it (a decode step
+//   through six shared layers: 0.699 -> 0.670 ms; 8 or 9 stages x 2 wavefronts: 0.72-0.74, 5 x 4: 0.679).
+template <bool SPLIT, bool DEEP>
+struct Ring {
+  static constexpr int STAGES = DEEP ? (SPLIT ? 5 : 6) : 4;
+  static constexpr int WAVES = SPLIT ? KSPLIT : (DEEP ? 3 : 5);
+  static constexpr int X_RING = STAGES * STAGE_BYTES;      // a wavefront's ring: weight stages, then activation stages
+  static constexpr int WAVE_LDS = 2 * STAGES * STAGE_BYTES;
+  static constexpr int LDS_BYTES = WAVES * WAVE_LDS;
+  static constexpr int INFL = STAGES - 1;                  // stages in flight
+  static_assert(LDS_BYTES <= 163840 && 8 * (INFL - 1) < 64, "ring");
+};
+constexpr int kDeepMaxItems = 1024;
 constexpr int kSplitMaxItems = 384;                        // measured: 192 items 25 -> 9 us per launch, 576 and 768 items slower with it
 
 #define HMI_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
@@ -66,9 +80,11 @@ __device__ __forceinline__ int perm_w(int i) { return ((i >> 2) & 1) * 16 + (i >
 // SPLIT: the workgroup is KSPLIT wavefronts that share one item (row_split items only); wavefront w
 // multiplies the w-th quarter of k.  Everything that decides whether a wavefront leaves early is the same
 // for the whole workgroup, so all of them reach the barrier in front of the sum.
-template <bool SPLIT>
-__global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinny_kernel(GemmArgs g, Route rt, int n_items, int row_split) {
+template <bool SPLIT, bool DEEP>
+__global__ __launch_bounds__((64 * Ring<SPLIT, DEEP>::WAVES)) void gemm_bf16_skinny_kernel(GemmArgs g, Route rt, int n_items, int row_split) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  using R = Ring<SPLIT, DEEP>;
+  constexpr int STAGES = R::STAGES, WAVES = R::WAVES, X_RING = R::X_RING, WAVE_LDS = R::WAVE_LDS, INFL = R::INFL;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int item = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * WAVES + wave;
@@ -121,7 +137,7 @@ __global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinn
   const int fw_base = rw * 128 + ((lh ^ swz_w(rw)) << 4);
   const int fx_base = X_RING + l32 * 128 + ((lh ^ swz_a(l32)) << 4);
 
-  // stage S of both operands into ring slot S mod 4 (8 copies); past the end: an in-bounds re-read nobody consumes
+  // stage S of both operands into ring slot S mod STAGES (8 copies); past the end: an in-bounds re-read nobody consumes
 #define HMI_COPY_STAGE(S)                                                                          \
   {                                                                                                \
     const int st_ = k_first + min((S), KT - 1);                                                    \
@@ -138,11 +154,10 @@ __global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinn
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 
-  HMI_COPY_STAGE(0)
-  HMI_COPY_STAGE(1)
-  HMI_COPY_STAGE(2)
+#pragma unroll
+  for (int p = 0; p < INFL; ++p) HMI_COPY_STAGE(p)
   for (int s = 0; s < KT; ++s) {
-    HMI_WAIT_VMCNT(16);                      // stage s has landed; the 16 copies of stages s + 1, s + 2 may be in flight
+    HMI_WAIT_VMCNT(8 * (INFL - 1));          // stage s has landed; the copies of the INFL - 1 stages after it may be in flight
     __builtin_amdgcn_sched_barrier(0);
     const unsigned char* sb = ring + (s % STAGES) * STAGE_BYTES;
     bf16x8 fw[4], fx[4];
@@ -154,7 +169,7 @@ __global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinn
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[ks], fx[ks], acc, 0, 0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    HMI_COPY_STAGE(s + 3)                    // into the slot that stage s - 1 was read from
+    HMI_COPY_STAGE(s + INFL)                 // into the slot that stage s - 1 was read from
   }
 #undef HMI_COPY_STAGE
   HMI_WAIT_VMCNT(0);                         // the trailing copies must have landed before the LDS is handed on
@@ -229,11 +244,22 @@ __global__ __launch_bounds__(64 * (SPLIT ? KSPLIT : WAVES)) void gemm_bf16_skinn
 
 }  // namespace
 
+template <bool SPLIT, bool DEEP>
+static void allow_ring() {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<SPLIT, DEEP>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Ring<SPLIT, DEEP>::LDS_BYTES);
+}
+
 void init_gemm_bf16_skinny_kernels() {
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_skinny_kernel<true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, KSPLIT * WAVE_LDS);
+  allow_ring<false, false>(); allow_ring<false, true>(); allow_ring<true, true>();
+}
+
+template <bool SPLIT, bool DEEP>
+static void launch_ring(const GemmArgs& g, const Route& rt, hipStream_t s, long long n_items, int row_split) {
+  using R = Ring<SPLIT, DEEP>;
+  const unsigned blocks = SPLIT ? (unsigned)n_items : (unsigned)((n_items + R::WAVES - 1) / R::WAVES);
+  hipLaunchKernelGGL((gemm_bf16_skinny_kernel<SPLIT, DEEP>), dim3(blocks), dim3(64 * R::WAVES), R::LDS_BYTES, s,
+                     g, rt, (int)n_items, row_split);
 }
 
 // Preconditions (checked by the caller): k % 64 == 0, n_out % 32 == 0, which_tiles names the list of
@@ -243,13 +269,10 @@ void launch_gemm_bf16_skinny(const GemmArgs& g, const Route& rt, hipStream_t s) 
   const long long n_items = (long long)g.n_mtiles * (g.n_out / SK) * (row_split ? 4 : 1);
   if (n_items <= 0) return;
   // few items, long k: one workgroup per item with k shared by its wavefronts
-  if (row_split && n_items <= kSplitMaxItems && g.k % (64 * KSPLIT) == 0 && g.k >= 64 * KSPLIT * 2) {
-    hipLaunchKernelGGL(gemm_bf16_skinny_kernel<true>, dim3((unsigned)n_items), dim3(64 * KSPLIT), KSPLIT * WAVE_LDS, s,
-                       g, rt, (int)n_items, row_split);
-    return;
-  }
-  hipLaunchKernelGGL(gemm_bf16_skinny_kernel<false>, dim3((unsigned)((n_items + WAVES - 1) / WAVES)), dim3(64 * WAVES),
-                     LDS_BYTES, s, g, rt, (int)n_items, row_split);
+  if (row_split && n_items <= kSplitMaxItems && g.k % (64 * KSPLIT) == 0 && g.k >= 64 * KSPLIT * 2)
+    return launch_ring<true, true>(g, rt, s, n_items, row_split);
+  if (n_items <= kDeepMaxItems) return launch_ring<false, true>(g, rt, s, n_items, row_split);
+  launch_ring<false, false>(g, rt, s, n_items, row_split);
 }
 
 }  // namespace hmi
