@@ -38,13 +38,13 @@ constexpr int STAGE_BYTES = SK * 128;                      // per operand: 32 ro
 constexpr int KSPLIT = 4;                                  // wavefronts that share the k of one item in the split variant
 // Ring depth and wavefronts per workgroup (always 160 KB of LDS, or all the split variant can use):
 //   4 stages x 5 wavefronts: launches with many items (per-tenant decode steps), bound by streaming the weights;
-//   6 stages x 3 wavefronts, 5 stages in the split variant: launches with at most kDeepMaxItems items (shared layers,
+//   6 stages x 3 wavefronts (the split variant keeps 4 stages: 5 were 3 % slower): launches with at most kDeepMaxItems items (shared layers,
 //   a few hundred rows): there a launch lasts as long as one wavefront's walk over k, a chain of
 //   k / 64 / (stages in flight) round trips to L2 or beyond, so more stages in flight shorten it (a decode step
 //   through six shared layers: 0.699 -> 0.670 ms; 8 or 9 stages x 2 wavefronts: 0.72-0.74, 5 x 4: 0.679).
 template <bool SPLIT, bool DEEP>
 struct Ring {
-  static constexpr int STAGES = DEEP ? (SPLIT ? 5 : 6) : 4;
+  static constexpr int STAGES = (DEEP && !SPLIT) ? 6 : 4;
   static constexpr int WAVES = SPLIT ? KSPLIT : (DEEP ? 3 : 5);
   static constexpr int X_RING = STAGES * STAGE_BYTES;      // a wavefront's ring: weight stages, then activation stages
   static constexpr int WAVE_LDS = 2 * STAGES * STAGE_BYTES;
