@@ -130,6 +130,13 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) 
     }
     slot_base = (size_t)rt.seg_slot[lo] * a.slot_stride;
   }
+  // gain and shift are asked for before the statistics are reduced: they arrive under the reductions
+  f32x4 gg[NV], bb[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    gg[i] = load4(a.pool + slot_base + a.g_off, i * 256 + lane * 4, !BF16);
+    bb[i] = load4(a.pool + slot_base + a.b_off, i * 256 + lane * 4, !BF16);
+  }
   float s = 0.0f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
@@ -146,11 +153,9 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(LnArgs a, Route rt) 
   for (int i = 0; i < NV; ++i)
     {
       const int col = i * 256 + lane * 4;
-      const f32x4 gg = load4(a.pool + slot_base + a.g_off, col, !BF16);
-      const f32x4 bb = load4(a.pool + slot_base + a.b_off, col, !BF16);
       f32x4 y;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) y[e] = (v[i][e] - mean) * rstd * gg[e] + bb[e];
+      for (int e = 0; e < 4; ++e) y[e] = (v[i][e] - mean) * rstd * gg[i][e] + bb[i][e];
       const size_t idx = row * d + col;
       if (a.out_f32) *reinterpret_cast<f32x4*>(a.out_f32 + idx) = y;
       if (a.out_st) {
