@@ -46,14 +46,32 @@ __device__ __forceinline__ int block_exscan(int v, int* wave_tot, int& total) {
   return base + inc - v;
 }
 
+// The same for two values at once (one pair of barriers for both).
+__device__ __forceinline__ void block_exscan2(int v0, int v1, int* wave_tot, int& ex0, int& ex1, int& total0, int& total1) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int inc0 = wave_incl_scan(v0, lane), inc1 = wave_incl_scan(v1, lane);
+  if (lane == 63) { wave_tot[w] = inc0; wave_tot[kWaves + w] = inc1; }
+  __syncthreads();
+  int base0 = 0, base1 = 0, tot0 = 0, tot1 = 0;
+#pragma unroll
+  for (int i = 0; i < kWaves; ++i) {
+    const int t0 = wave_tot[i], t1 = wave_tot[kWaves + i];
+    if (i < w) { base0 += t0; base1 += t1; }
+    tot0 += t0; tot1 += t1;
+  }
+  __syncthreads();
+  total0 = tot0; total1 = tot1;
+  ex0 = base0 + inc0 - v0; ex1 = base1 + inc1 - v1;
+}
+
 __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R, int key_bits) {
   __shared__ int key[2][kMaxRequests];
   __shared__ int val[2][kMaxRequests];
   __shared__ int tok_s[kMaxRequests + 1];     // request -> first original row
   __shared__ int stok_s[kMaxRequests + 1];    // sorted position -> first sorted row
   __shared__ int segtok_s[kMaxRequests + 1];  // segment -> first sorted row
-  __shared__ int cnt[16 * kRounds * kWaves];
-  __shared__ int wave_tot[kWaves];
+  __shared__ int cnt[64 * kRounds * kWaves];   // per digit, round and wavefront: 6-bit digits at most
+  __shared__ int wave_tot[2 * kWaves];
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int rounds = (R + kRouterThreads - 1) / kRouterThreads;
@@ -87,10 +105,14 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
   }
   __syncthreads();
 
-  // ---- stable LSD radix sort of (tenant id, request) by tenant id
+  // ---- stable LSD radix sort of (tenant id, request) by tenant id: as few passes as digits of at most
+  //      6 bits allow (64 tenants: one pass, 1 000: two, 10 000: three), all passes equally wide
   int cur = 0;
-  const int ncnt = 16 * rounds * kWaves;  // <= 1024
-  for (int shift = 0; shift < key_bits; shift += 4) {
+  const int passes = (key_bits + 5) / 6;
+  const int db = passes > 0 ? (key_bits + passes - 1) / passes : 0;      // bits per digit
+  const int stride = rounds * kWaves;                                    // counters per digit value
+  const int ncnt = (1 << db) * stride;                                   // <= 2048
+  for (int shift = 0; shift < passes * db; shift += db) {
     for (int i = tid; i < ncnt; i += kRouterThreads) cnt[i] = 0;
     __syncthreads();
     int digit[kRounds], rank[kRounds], k_[kRounds], v_[kRounds];
@@ -101,31 +123,35 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
         int i = c * kRouterThreads + tid;
         bool valid = i < R;
         if (valid) { k_[c] = key[cur][i]; v_[c] = val[cur][i]; }
-        int dg = valid ? ((k_[c] >> shift) & 15) : 0;
+        int dg = valid ? ((k_[c] >> shift) & ((1 << db) - 1)) : 0;
         unsigned long long mask = __ballot(valid);
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          bool bit = (dg >> b) & 1;
-          unsigned long long bal = __ballot(valid && bit);
-          mask &= bit ? bal : ~bal;
+        for (int b = 0; b < 6; ++b) {
+          if (b < db) {
+            bool bit = (dg >> b) & 1;
+            unsigned long long bal = __ballot(valid && bit);
+            mask &= bit ? bal : ~bal;
+          }
         }
         if (valid) {
           digit[c] = dg;
           rank[c] = __popcll(mask & ((1ull << lane) - 1ull));
-          if (rank[c] == 0) cnt[dg * (rounds * kWaves) + c * kWaves + w] = __popcll(mask);
+          if (rank[c] == 0) cnt[dg * stride + c * kWaves + w] = __popcll(mask);
         }
       }
     }
     __syncthreads();
+    // exclusive scan over the counters in (digit, round, wavefront) order, two neighbours per lane
     int tot;
-    int mine = tid < ncnt ? cnt[tid] : 0;
-    int ex = block_exscan(mine, wave_tot, tot);
-    if (tid < ncnt) cnt[tid] = ex;
+    const int c0 = 2 * tid < ncnt ? cnt[2 * tid] : 0, c1 = 2 * tid + 1 < ncnt ? cnt[2 * tid + 1] : 0;
+    const int ex = block_exscan(c0 + c1, wave_tot, tot);
+    if (2 * tid < ncnt) cnt[2 * tid] = ex;
+    if (2 * tid + 1 < ncnt) cnt[2 * tid + 1] = ex + c0;
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < kRounds; ++c) {
       if (c < rounds && digit[c] >= 0) {
-        int pos = cnt[digit[c] * (rounds * kWaves) + c * kWaves + w] + rank[c];
+        int pos = cnt[digit[c] * stride + c * kWaves + w] + rank[c];
         key[cur ^ 1][pos] = k_[c];
         val[cur ^ 1][pos] = v_[c];
       }
@@ -150,9 +176,9 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
     bool in = p < R;
     int head = in && (p == 0 || sid[p] != sid[p - 1]);
     int len = in ? tok_s[perm[p] + 1] - tok_s[perm[p]] : 0;
-    int tot_h, tot_l;
-    int g = block_exscan(head, wave_tot, tot_h) + seg_carry;
-    int st = block_exscan(len, wave_tot, tot_l) + tok_carry;
+    int tot_h, tot_l, g, st;
+    block_exscan2(head, len, wave_tot, g, st, tot_h, tot_l);
+    g += seg_carry; st += tok_carry;
     if (in) {
       rt.perm[p] = perm[p];
       stok_s[p] = st;
@@ -177,31 +203,42 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
   }
   __syncthreads();
 
-  // ---- m-tile work lists: tiles never straddle a segment
-  for (int h = 0; h < 2; ++h) {
-    const int tm = rt.tile_m[h];
-    if (tm <= 0) continue;
-    int tile_carry = 0;
+  // ---- m-tile work lists for both tile heights: tiles never straddle a segment
+  {
+    const int tm0 = rt.tile_m[0], tm1 = rt.tile_m[1];
+    int carry0 = 0, carry1 = 0;
     const int grounds = (G + kRouterThreads - 1) / kRouterThreads;
     for (int c = 0; c < grounds; ++c) {
-      int g = c * kRouterThreads + tid;
-      int rows = g < G ? segtok_s[g + 1] - segtok_s[g] : 0;
-      int nt = (rows + tm - 1) / tm;
-      int tot;
-      int base = block_exscan(nt, wave_tot, tot) + tile_carry;
-      for (int t = 0; t < nt; ++t) {
-        rt.tile_seg[h][base + t] = g;
-        rt.tile_row0[h][base + t] = segtok_s[g] + t * tm;
-      }
-      tile_carry += tot;
+      const int g = c * kRouterThreads + tid;
+      const int first = g < G ? segtok_s[g] : 0;
+      const int rows = g < G ? segtok_s[g + 1] - first : 0;
+      const int nt0 = tm0 > 0 ? (rows + tm0 - 1) / tm0 : 0, nt1 = tm1 > 0 ? (rows + tm1 - 1) / tm1 : 0;
+      int base0, base1, tot0, tot1;
+      block_exscan2(nt0, nt1, wave_tot, base0, base1, tot0, tot1);
+      base0 += carry0; base1 += carry1;
+      for (int t = 0; t < nt0; ++t) { rt.tile_seg[0][base0 + t] = g; rt.tile_row0[0][base0 + t] = first + t * tm0; }
+      for (int t = 0; t < nt1; ++t) { rt.tile_seg[1][base1 + t] = g; rt.tile_row0[1][base1 + t] = first + t * tm1; }
+      carry0 += tot0; carry1 += tot1;
     }
-    if (tid == 0) rt.n_tiles[h][0] = tile_carry;
+    if (tid == 0) {
+      if (tm0 > 0) rt.n_tiles[0][0] = carry0;
+      if (tm1 > 0) rt.n_tiles[1][0] = carry1;
+    }
   }
 
-  // ---- sorted row -> original row, one wavefront per request
-  for (int p = w; p < R; p += kWaves) {
-    const int src0 = tok_s[perm[p]], dst0 = stok_s[p], len = stok_s[p + 1] - dst0;
-    for (int i = lane; i < len; i += 64) rt.row_src[dst0 + i] = src0 + i;
+  // ---- sorted row -> original row.  Wavefront w takes the sorted positions w, w + 16, ...: a lane first fetches
+  //      the three numbers of one of them (a dependent chain through LDS, once for 64 positions), then the
+  //      wavefront walks over those 64 with the numbers broadcast from that lane's registers.
+  for (int base = 0; base < R; base += kWaves * 64) {
+    const int myp = base + lane * kWaves + w;
+    int src0 = 0, dst0 = 0, len = 0;
+    if (myp < R) { src0 = tok_s[perm[myp]]; dst0 = stok_s[myp]; len = stok_s[myp + 1] - dst0; }
+    const int mine = min(64, (R - base - w + kWaves - 1) / kWaves);      // positions of this wavefront in this batch of 1024
+    for (int l = 0; l < mine; ++l) {
+      const int s0 = __builtin_amdgcn_readlane(src0, l), d0 = __builtin_amdgcn_readlane(dst0, l);
+      const int n = __builtin_amdgcn_readlane(len, l);
+      for (int i = lane; i < n; i += 64) rt.row_src[d0 + i] = s0 + i;
+    }
   }
 }
 
