@@ -393,6 +393,7 @@ def main() -> int:
         "decode": decode,
         "vendor_dense_gemm": vendor,
         "parity_note": parity_note,
+        "library_override": os.environ.get("HMI_LIB_PATH") or None,   # set: another build of the library was timed (e.g. an ablation)
         "request_path": pipeline,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -1,7 +1,10 @@
 """Builds libhmi.so (the C-ABI library: HIP kernels + pool) in-tree for gfx950.
 
     python paper_2504_17449_amd/build.py
+    python paper_2504_17449_amd/build.py --lib /tmp/libhmi_x.so --obj-suffix _x -DHMI_ABLATE_MFMA=1
 
+The second form writes another library (load it with HMI_LIB_PATH=...) from the same sources with extra
+compiler flags: the timing-only ablation builds of the persistent GEMM are made this way.
 hipcc cross-compiles without a GPU.  Packed-fp32 code generation is switched off for the
 device pass, as required on the target machines.
 """
@@ -44,5 +47,10 @@ def build(verbose: bool = True, lib: str = LIB, extra_flags=(), obj_suffix: str 
 
 
 if __name__ == "__main__":
-    build()
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--lib", default=LIB)
+    ap.add_argument("--obj-suffix", default="")
+    ns, extra = ap.parse_known_args()
+    build(lib=ns.lib, extra_flags=extra, obj_suffix=ns.obj_suffix)
     sys.exit(0)

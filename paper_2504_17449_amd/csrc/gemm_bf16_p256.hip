@@ -101,6 +101,29 @@ __device__ __forceinline__ int swz_w(int row) { return ((row >> 1) & 3) | (((row
 // so that output register r of lane half h is column 16 h + r.
 __device__ __forceinline__ int perm_w(int i) { return ((i >> 2) & 1) * 16 + (i >> 3) * 4 + (i & 3); }
 
+// Timing-only ablations of the main loop (never set by the build script's defaults; RESULTS ARE WRONG with any of them):
+//   -DHMI_ABLATE_MFMA=1    no MFMA is issued (fragments are still read from LDS)
+//   -DHMI_ABLATE_READS=1   no fragment is read from LDS
+//   -DHMI_ABLATE_COPIES=1  the steady-state stages issue no copy (prologues and tile changes still do)
+//   -DHMI_ABLATE_WAIT=n    a stage waits until all but n (instead of one) operand stages of copies have landed
+// They exist so that the time of each part of a stage can be measured with the launch shapes, addresses
+// and tile order of the real kernel; every access they leave in is one the real kernel makes.
+#ifndef HMI_ABLATE_MFMA
+#define HMI_ABLATE_MFMA 0
+#endif
+#ifndef HMI_ABLATE_READS
+#define HMI_ABLATE_READS 0
+#endif
+#ifndef HMI_ABLATE_COPIES
+#define HMI_ABLATE_COPIES 0
+#endif
+#ifndef HMI_ABLATE_WAIT
+#define HMI_ABLATE_WAIT 1
+#endif
+#if HMI_ABLATE_MFMA || HMI_ABLATE_READS || HMI_ABLATE_COPIES || HMI_ABLATE_WAIT != 1
+#warning "gemm_bf16_p256: timing-only ablation build, results are wrong"
+#endif
+
 #define HMI_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 #define HMI_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
@@ -243,16 +266,22 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
 
   // loads the MFMA fragments of k-step KS of the stage in slots a_rd / w_rd into register buffer B
 #define HMI_READ_FRAGS(B, KS)                                                                     \
-  {                                                                                               \
+  if (!HMI_ABLATE_READS) {                                                                                               \
     const unsigned char* xa_ = smem + a_rd + (fx_base ^ ((KS) << 5));                             \
     const unsigned char* wa_ = smem + w_rd + (fw_base ^ ((KS) << 5));                             \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) fx[B][i] = *reinterpret_cast<const bf16x8*>(xa_ + i * 32 * ROW_BYTES); \
     _Pragma("unroll") for (int j = 0; j < TN; ++j) fw[B][j] = *reinterpret_cast<const bf16x8*>(wa_ + j * 32 * ROW_BYTES); \
   }
+#if HMI_ABLATE_MFMA
+#define HMI_MFMAS(B)   /* keeps the fragment registers (and so their reads) alive */                  \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i) asm volatile("" :: "v"(fx[B][i]));               \
+  _Pragma("unroll") for (int j = 0; j < TN; ++j) asm volatile("" :: "v"(fw[B][j]));
+#else
 #define HMI_MFMAS(B)                                                                              \
   _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                  \
     _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                \
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[B][j], fx[B][i], acc[i][j], 0, 0, 0);
+#endif
 
   // scheduling: each of the 6 fragment reads of the next k-step goes behind one MFMA of
   // this k-step (the wait for this k-step's fragments then comes before any new read)
@@ -285,7 +314,7 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
   //   3: (s = KT-1) none: the freed slots serve the epilogue first
 #define HMI_STAGE_COPIES(MODE)                                                                    \
   {                                                                                               \
-    if (MODE == 0) { HMI_COPY4(Ab + (s + 2) * ROW_BYTES, cur.a_off, fa_) HMI_COPY4(cur.Wb + (s + 3) * ROW_BYTES, b_off, W_RING + fw_) } \
+    if (MODE == 0 && !HMI_ABLATE_COPIES) { HMI_COPY4(Ab + (s + 2) * ROW_BYTES, cur.a_off, fa_) HMI_COPY4(cur.Wb + (s + 3) * ROW_BYTES, b_off, W_RING + fw_) } \
     if (MODE == 1) { HMI_COPY4(Ab + (s + 2) * ROW_BYTES, cur.a_off, fa_) HMI_COPY4(nxt.Wb, b_off, W_RING + fw_) }                     \
     if (MODE == 2) { HMI_COPY4(Ab, nxt.a_off, fa_) HMI_COPY4(nxt.Wb + ROW_BYTES, b_off, W_RING + fw_) }                                \
   }
@@ -304,7 +333,7 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
     }                                                                                             \
     HMI_WAIT_LGKMCNT0();          /* this wavefront no longer reads stage s from LDS */           \
     if (MODE == 2 && wave == 0) { HMI_WAIT_VMCNT(0); }   /* ... and its mailbox store is done */   \
-    else { HMI_WAIT_VMCNT(LD); }  /* its copies of stage s+1 (both operands) have landed */       \
+    else { HMI_WAIT_VMCNT(HMI_ABLATE_WAIT * LD); }  /* its copies of stage s+1 (both operands) have landed */       \
     __builtin_amdgcn_s_barrier(); /* ... everybody's, and nobody reads stage s any more */        \
     __builtin_amdgcn_sched_barrier(0);                                                            \
     if (MODE == 1 && claimer) __hip_atomic_store(mailbox, claimed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); \
