@@ -131,6 +131,8 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 // What a lane needs to know about a tile: where its copies come from and where the bias is.
+constexpr int kMBlock = 8;   // m-tiles per block of a long segment's tile order
+
 template <int NW>
 struct TileRegs {
   int n0, row0, rows;
@@ -153,8 +155,13 @@ __device__ __forceinline__ void load_tile(const GemmArgs& g, const Route& rt, in
   const int mt_first = mt_any - (rt.tile_row0[g.which_tiles][mt_any] - s0) / BM;
   const int mt_cnt = (s1 - s0 + BM - 1) / BM;
   const int q = w - mt_first * nt_n;
-  tr.n0 = (q / mt_cnt) * BN;
-  tr.row0 = s0 + (q % mt_cnt) * BM;
+  // A long segment goes block by block of kMBlock m-tiles (the last block may be shorter): an activation panel's
+  // n-tiles are then at most kMBlock tiles apart, close enough to run in the same round of the XCD's workgroups.
+  const int b = q / (kMBlock * nt_n);
+  const int bm = b < mt_cnt / kMBlock ? kMBlock : mt_cnt - b * kMBlock;
+  const int rem = q - b * (kMBlock * nt_n);
+  tr.n0 = (rem / bm) * BN;
+  tr.row0 = s0 + (b * kMBlock + rem % bm) * BM;
   tr.rows = min(BM, s1 - tr.row0);
   const size_t slot_base = (size_t)rt.seg_slot[seg] * g.slot_stride;
   tr.Wb = g.pool + slot_base + g.w_off + (size_t)tr.n0 * (size_t)(g.k * 2);

@@ -127,6 +127,19 @@ def test_persistent_gemm_more_tiles_than_workgroups(hmi):
                         hbm_slots=300, seq_min=1, seq_max=5, popularity="uniform"), batch=1)
 
 
+@pytest.mark.parametrize("seed", [15, 10])
+def test_persistent_gemm_long_segments_in_blocks_of_m_tiles(hmi, seed):
+    """Two tenants with thousands of rows each.  The persistent GEMM walks a long segment in blocks of
+    eight m-tiles of 256 rows; seed 15 gives segments of 8 and 11 m-tiles (exactly one block; one block and a
+    short one of three), seed 10 gives 16 and 5 (two full blocks; less than one), each with a ragged last
+    tile.  Every row compared."""
+    wl = small(synth.BLOCK_FFN, "bf16", d_model=256, d_ff=768, n_requests=24, n_tenants=2, hbm_slots=2,
+               seq_min=100, seq_max=300, popularity="uniform", seed=seed)
+    ids, lens = synth.batch_ids_lens(wl, 0)
+    assert sorted(-(-int(lens[ids == t].sum()) // 256) for t in range(2)) == {15: [8, 11], 10: [5, 16]}[seed]
+    run_case(hmi, wl)
+
+
 def test_second_layer_alone(hmi):
     """forward(layer=1) uses layer 1's weights: equals the oracle fed layer-1 weights only."""
     from paper_2504_17449_amd import harness
