@@ -67,7 +67,7 @@ enum { HMI_BLOCK_FFN = 0, HMI_BLOCK_ENC_POSTLN = 1, HMI_BLOCK_DEC_PRELN = 2, HMI
 typedef struct {
   int32_t block;        /* HMI_BLOCK_*                                                    */
   int32_t dtype;        /* HMI_F32 | HMI_BF16: storage type of weights, x and y           */
-  int32_t d_model;      /* multiple of 64 (bf16) / 16 (f32); max_tokens * max(d_model, d_ff)
+  int32_t d_model;      /* multiple of 64 (bf16) / 16 (f32), at most 2048; max_tokens * max(d_model, d_ff)
                            * element size must stay below 4 GiB (32-bit row offsets)      */
   int32_t d_ff;         /* FFN width, or adapter rank; multiple of 64 (bf16) / 16 (f32)   */
   int32_t n_heads;      /* attention blocks: d_model / n_heads must be 64; else 0         */

@@ -12,6 +12,10 @@ import os
 from typing import Optional, Sequence
 
 import numpy as np
+# Before the library is loaded: torch ships its own HIP runtime, and the device buffers and streams the calls
+# below receive come from it.  The library has to bind to that same runtime; loaded first, it would bring in the
+# system's, and the second runtime to initialise in a process finds no device.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("HMI_LIB_PATH") or os.path.join(_HERE, "libhmi.so")  # override: alternative builds

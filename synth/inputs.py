@@ -183,6 +183,8 @@ def _offset(seed: int, tag: int, a: int, b: int, c: int, n: int) -> int:
     k = _mix64(seed ^ 0x5851F42D4C957F2D)
     for v in (tag, a, b, c):
         k = _mix64(k ^ int(v))
+    if n >= _MASTER_LEN:
+        raise ValueError(f"a tensor of {n} elements does not fit the generator's master sequence of {_MASTER_LEN} draws")
     return k % (_MASTER_LEN - n)
 
 

@@ -52,6 +52,19 @@ def test_argument_errors_need_no_gpu():
     assert pkg.lib.hmi_queue_destroy(None) == pkg.HMI_OK
 
 
+def test_binding_loads_torch_before_the_library():
+    """Buffers and streams come from torch, so the library must bind to the HIP runtime torch ships: the binding
+    imports torch before it loads libhmi.so (the other order leaves two runtimes in the process)."""
+    import subprocess
+    import sys
+    code = ("import sys; import paper_2504_17449_amd as p; assert 'torch' in sys.modules; "
+            "maps = open('/proc/self/maps').read(); hip = sorted({l.split()[-1] for l in maps.splitlines() if 'libamdhip64' in l}); "
+            "assert len(hip) == 1, hip; print(hip[0])")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300, cwd=ROOT)
+    assert r.returncode == 0, r.stderr
+    assert "/torch/" in r.stdout, r.stdout
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU: any other --gpus exits non-zero with a message that says so, before torch is imported."""
     import subprocess

@@ -140,6 +140,45 @@ def test_persistent_gemm_long_segments_in_blocks_of_m_tiles(hmi, seed):
     run_case(hmi, wl)
 
 
+def test_decoder_layer_at_the_maximum_width(hmi):
+    """d_model = 2048 (the widest the library takes), f = 6144, 32 heads, prompts of up to 1500 tokens, pre-LN
+    decoder: outputs are not normalised (|y| up to 7.6), so storing y as bf16 costs up to 0.0156 by itself.  The
+    fp32 result is held to the flat bars; the bf16 result is that one rounded once, bit for bit, and every element
+    is within the flat bar plus half a bf16 unit of its value."""
+    from paper_2504_17449_amd import harness
+    from tests.oracle_side import within_storage_rounding
+    wl = small(synth.BLOCK_DEC_PRELN, "bf16", d_model=2048, d_ff=6144, n_heads=32, n_tenants=3, hbm_slots=3,
+               n_requests=6, seq_min=1, seq_max=1500)
+    ids, lens, x = harness.batch_to_device(wl, 0)
+    pool = harness.create_pool(wl, max_requests=len(ids), max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl, sorted(set(ids.tolist())))
+        y = torch.empty_like(x)
+        y32 = torch.empty(x.shape, dtype=torch.float32, device=x.device)
+        pool.forward(0, x, y, ids, lens)
+        pool.stack_forward_f32(0, 1, x, y32, ids, lens)
+        torch.cuda.synchronize()
+        check_route(pool, ids, lens)
+        assert torch.equal(y32.to(torch.bfloat16).view(torch.int16), y.view(torch.int16))
+        yb, yf = harness.device_to_f64(y), y32.double().cpu().numpy()
+    finally:
+        pool.close()
+    ref = oracle_forward(wl, ids, lens, list(range(len(ids))), 0)
+    rows = np.arange(len(ref))
+    max_abs, rel, ok = compare(yf, ref, rows, "bf16")
+    print(f"  fp32 result: max_abs={max_abs:.3e} rel_fro={rel:.3e} max|y_ref|={np.abs(ref).max():.2f}", flush=True)
+    assert ok, (max_abs, rel)
+    assert within_storage_rounding(yb, ref, rows)
+    assert compare(yb, ref, rows, "bf16")[1] <= 1e-2
+
+
+def test_request_limit_of_one_or_two_tokens_each(hmi):
+    """2048 requests (the most a call takes) of one or two tokens of 500 tenants through a decoder layer:
+    attention over one or two keys, segments of a few rows, every row compared."""
+    run_case(hmi, small(synth.BLOCK_DEC_PRELN, "bf16", d_model=128, d_ff=256, n_heads=2, n_tenants=500, hbm_slots=500,
+                        n_requests=2048, seq_min=1, seq_max=2))
+
+
 def test_second_layer_alone(hmi):
     """forward(layer=1) uses layer 1's weights: equals the oracle fed layer-1 weights only."""
     from paper_2504_17449_amd import harness
