@@ -315,6 +315,47 @@ def test_host_tier_tiny_cache_evicts_every_batch(slots):
         pool.close()
 
 
+@pytest.mark.parametrize("host_tier", [False, True])
+def test_loading_a_tenant_again_replaces_its_weights(host_tier):
+    """Re-loading a (tenant, layer) replaces its weights (Sec. 4.1: an instance is created from stored parameters; a
+    tenant that fine-tunes again registers new ones).  Tenants get other tenants' generated weights right after a
+    forward that read the old ones was enqueued, with nothing synchronised in between; the next forward must use
+    the new weights for every layer, for a resident tenant and (host tier, 3 slots for 6 tenants) for one that is
+    only in pinned host memory at that moment."""
+    from paper_2504_17449_amd import harness
+    slots = 3 if host_tier else 6
+    wl = synth.Workload("reload", synth.BLOCK_ENC_POSTLN, "bf16", 128, 256, 2, 2, 6, 9, 1, 60,
+                        "uniform", 0.0, 1e-5, slots, host_tier, seed=21)
+    _, lens, x = harness.batch_to_device(wl, 0)
+    ids = np.array([1, 3, 1, 5, 3, 5, 1, 1, 3], np.int32)          # three distinct tenants: fits three slots
+    pool = harness.create_pool(wl, max_requests=len(ids), max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl)
+
+        def forward_and_check(ids, weights_from, what):
+            y = torch.empty_like(x)
+            pool.stack_forward(0, wl.n_layers, x, y, ids, lens)
+            return y, oracle_forward(wl, np.array([weights_from.get(int(t), int(t)) for t in ids], np.int32), lens), what
+
+        runs = [forward_and_check(ids, {}, "as loaded")]
+        # tenant 1 is resident and was just read; tenant 4 is not in this batch (host tier: not resident either)
+        for t, src in ((1, 4), (4, 0)):
+            for l in range(wl.n_layers):
+                pool.load_tenant(t, l, synth.tenant_storage(wl, src, l))
+        runs.append(forward_and_check(ids, {1: 4, 4: 0}, "tenant 1 replaced"))
+        ids2 = np.array([4, 1, 4, 0, 0, 4, 1, 0, 4], np.int32)
+        runs.append(forward_and_check(ids2, {1: 4, 4: 0}, "tenants 1 and 4 replaced, 4 swapped in"))
+        torch.cuda.synchronize()
+        for y, y_ref, what in runs:
+            max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, np.arange(len(y_ref)), wl.dtype)
+            print(f"  {what}: max_abs={max_abs:.3e} rel_fro={rel:.3e}", flush=True)
+            assert ok, (what, max_abs, rel)
+        # the replacement is visible: tenant 1's rows changed between the first two runs
+        assert not torch.equal(runs[0][0][: int(lens[0])], runs[1][0][: int(lens[0])])
+    finally:
+        pool.close()
+
+
 def test_host_tier_zipf_batches_with_prefetch_bf16():
     """The 10k-tenant recipe at reduced size: 1 500 tenants in pinned host memory behind a
     160-slot HBM cache, Zipf 0.8 popularity, ragged lengths, two layers.  Batch b+1 is
