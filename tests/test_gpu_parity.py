@@ -650,6 +650,40 @@ def test_bert_ffn_full_size_every_request(hmi):
     run_case(hmi, synth.WORKLOADS["bert_ffn"], tenants="all")
 
 
+def test_two_pools_of_different_shapes_take_turns(hmi):
+    """Two pools alive at once (an FFN pool of width 256 on the torch stream, an encoder pool of width 512 on a
+    stream of its own), called alternately with nothing synchronised in between: per-pool state (routing arrays,
+    tile counters, workspaces) must not be shared, whatever the order the two streams run in."""
+    from paper_2504_17449_amd import harness
+    wa = small(synth.BLOCK_FFN, "bf16", d_model=256, d_ff=768, n_requests=30, n_tenants=5, hbm_slots=5, seed=31)
+    wb = small(synth.BLOCK_ENC_POSTLN, "bf16", d_model=512, d_ff=1024, n_heads=8, n_requests=12, n_tenants=3,
+               hbm_slots=3, seed=32)
+    side = torch.cuda.Stream()
+    batches_a = [harness.batch_to_device(wa, b) for b in range(3)]
+    batches_b = [harness.batch_to_device(wb, b) for b in range(3)]
+    pa = harness.create_pool(wa, max_tokens=max(int(l.sum()) for _, l, _ in batches_a))
+    with torch.cuda.stream(side):
+        pb = harness.create_pool(wb, max_tokens=max(int(l.sum()) for _, l, _ in batches_b))
+    try:
+        harness.load_tenants(pa, wa)
+        harness.load_tenants(pb, wb)
+        torch.cuda.synchronize()
+        outs = []
+        for b in range(3):
+            for pool, (ids, lens, x), wl in ((pa, batches_a[b], wa), (pb, batches_b[b], wb)):
+                y = torch.empty_like(x)
+                pool.forward(0, x, y, ids, lens)
+                outs.append((wl, b, ids, lens, y))
+        torch.cuda.synchronize()
+        for wl, b, ids, lens, y in outs:
+            y_ref = oracle_forward(wl, ids, lens, None, b)
+            max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, np.arange(len(y_ref)), "bf16")
+            assert ok, (wl.name, b, max_abs, rel)
+    finally:
+        pa.close()
+        pb.close()
+
+
 def test_single_request_and_single_tenant(hmi):
     run_case(hmi, small(synth.BLOCK_ENC_POSTLN, "bf16", n_requests=1, seq_min=5, seq_max=5))
     run_case(hmi, small(synth.BLOCK_DEC_PRELN, "bf16", n_tenants=1, hbm_slots=1, n_requests=9))
