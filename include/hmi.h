@@ -19,6 +19,7 @@
  *     its copy stream and events.  The caller owns x, y, index arrays, weight source
  *     buffers and the compute stream.
  *   - not thread-safe per pool; calls on one pool must come from one thread at a time.
+ *     Different pools may be used from different threads at the same time.
  */
 #ifndef HMI_H
 #define HMI_H
@@ -307,8 +308,8 @@ int32_t hmi_pool_profile_read(hmi_pool_t* pool, double* ms, int64_t* launches);
 /* Bytes of one (tenant, layer) image in HBM (tensors padded to 256 B). */
 int64_t hmi_pool_image_bytes(const hmi_pool_t* pool);
 
-/* Static string describing the last error on this pool (or the last create error when
- * pool is NULL).  Valid until the next call on the pool. */
+/* Static string describing the last error on this pool (or, when pool is NULL, the calling
+ * thread's last create error).  Valid until the next call on the pool (by that thread). */
 const char* hmi_last_error(const hmi_pool_t* pool);
 
 /* Deletes every instance of the pool (Sec. 4.1, "delete hPLM", for all of them at once): waits

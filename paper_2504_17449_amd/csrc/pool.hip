@@ -27,7 +27,7 @@ constexpr int kRing = 8;
 constexpr size_t kAlign = 256;
 constexpr int kArenaImages = 32;  // pinned host images per hipHostMalloc call
 
-char g_create_error[256] = "";
+thread_local char g_create_error[256] = "";   // why the calling thread's last hmi_pool_create failed
 
 // Limits of hmi_layer_forward_static and the layout of its routing arrays inside `scratch`.
 constexpr int kStaticMaxRequests = 256;

@@ -684,6 +684,53 @@ def test_two_pools_of_different_shapes_take_turns(hmi):
         pb.close()
 
 
+def test_two_host_threads_each_with_a_pool_of_its_own(hmi):
+    """Different pools may be used from different host threads at once: each thread creates its pool on a stream of
+    its own, loads tenants and runs three batches (ctypes drops the interpreter lock inside every call, so the two
+    threads really are inside the library together)."""
+    import threading
+    from paper_2504_17449_amd import harness
+    specs = [small(synth.BLOCK_FFN, "bf16", d_model=256, d_ff=768, n_requests=30, n_tenants=5, hbm_slots=5, seed=41),
+             small(synth.BLOCK_DEC_PRELN, "bf16", d_model=256, d_ff=512, n_heads=4, n_requests=16, n_tenants=4,
+                   hbm_slots=4, seed=42)]
+    batches = [[harness.batch_to_device(wl, b) for b in range(3)] for wl in specs]
+    torch.cuda.synchronize()
+    results, errors = [None, None], []
+    start = threading.Barrier(2)
+
+    def worker(i):
+        try:
+            wl = specs[i]
+            with torch.cuda.stream(torch.cuda.Stream()):
+                start.wait(timeout=60)
+                pool = harness.create_pool(wl, max_tokens=max(int(l.sum()) for _, l, _ in batches[i]))
+                try:
+                    harness.load_tenants(pool, wl, workers=2)
+                    outs = []
+                    for ids, lens, x in batches[i]:
+                        y = torch.empty_like(x)
+                        pool.forward(0, x, y, ids, lens)
+                        outs.append(y)
+                    torch.cuda.current_stream().synchronize()
+                    results[i] = [harness.device_to_f64(y) for y in outs]
+                finally:
+                    pool.close()
+        except BaseException as e:   # noqa: BLE001 - reported by the main thread
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=180)
+    assert not errors, errors
+    for i, wl in enumerate(specs):
+        for b, (ids, lens, _) in enumerate(batches[i]):
+            y_ref = oracle_forward(wl, ids, lens, None, b)
+            max_abs, rel, ok = compare(results[i][b], y_ref, np.arange(len(y_ref)), "bf16")
+            assert ok, (wl.name, b, max_abs, rel)
+
+
 def test_single_request_and_single_tenant(hmi):
     run_case(hmi, small(synth.BLOCK_ENC_POSTLN, "bf16", n_requests=1, seq_min=5, seq_max=5))
     run_case(hmi, small(synth.BLOCK_DEC_PRELN, "bf16", n_tenants=1, hbm_slots=1, n_requests=9))
