@@ -13,7 +13,9 @@
  *
  * Conventions for every entry point
  *   - plain C ABI; no exception crosses it; every call returns an int32 status
- *     (HMI_OK = 0, errors negative).  hmi_last_error() gives a readable reason.
+ *     (HMI_OK = 0, errors negative).  hmi_last_error() gives a readable reason.  A failed
+ *     HIP runtime call is reported as HMI_ERR_OOM / HMI_ERR_DEVICE and taken out of the
+ *     runtime's last-error state, so the caller's next hipGetLastError() does not see it.
  *   - "host" / "device" on a pointer says where the memory lives.
  *   - the library owns: the pool, its HBM slots, pinned host images, workspaces,
  *     its copy stream and events.  The caller owns x, y, index arrays, weight source

@@ -206,6 +206,9 @@ int32_t fail(hmi_pool* p, int32_t code, const char* fmt, ...) {
   va_start(ap, fmt);
   vsnprintf(p ? p->err : g_create_error, 256, fmt, ap);
   va_end(ap);
+  // A failed runtime call also stays behind as the runtime's "last error", where the caller's next, unrelated check
+  // (torch makes one after every operation) would find it: it has been reported through the status, so take it out.
+  if (code == HMI_ERR_OOM || code == HMI_ERR_DEVICE) (void)hipGetLastError();
   return code;
 }
 

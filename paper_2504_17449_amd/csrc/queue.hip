@@ -60,6 +60,7 @@ int32_t qfail(hmi_queue* q, int32_t code, const char* fmt, ...) {
   va_start(ap, fmt);
   vsnprintf(q->err, sizeof(q->err), fmt, ap);
   va_end(ap);
+  if (code == HMI_ERR_OOM || code == HMI_ERR_DEVICE) (void)hipGetLastError();   // reported here: not left for the caller's next check
   return code;
 }
 
@@ -115,7 +116,7 @@ int32_t hmi_queue_create(hmi_pool_t* pool, int32_t max_batch_requests, int32_t m
   q->row_bytes = (size_t)c->d_model * (c->dtype == HMI_BF16 ? 2 : 4);
   q->mark.assign(c->max_tenants, 0);
   q->ring.resize(max_waiting_batches + 2);
-  if (hipSetDevice(c->device) != hipSuccess) { delete q; return HMI_ERR_DEVICE; }
+  if (hipSetDevice(c->device) != hipSuccess) { delete q; (void)hipGetLastError(); return HMI_ERR_DEVICE; }
   for (auto& b : q->ring) {
     b.ids.resize(max_batch_requests);
     b.lens.resize(max_batch_requests);
@@ -126,6 +127,7 @@ int32_t hmi_queue_create(hmi_pool_t* pool, int32_t max_batch_requests, int32_t m
         hipMalloc(&b.x, (size_t)max_batch_tokens * q->row_bytes) != hipSuccess ||
         hipMalloc(&b.y, (size_t)max_batch_tokens * q->row_bytes) != hipSuccess) {
       hmi_queue_destroy(q);
+      (void)hipGetLastError();   // reported through the status: not left behind as the runtime's last error
       return HMI_ERR_OOM;
     }
   }

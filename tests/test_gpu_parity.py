@@ -779,3 +779,19 @@ def test_boundary_errors_and_empty_batch(hmi):
         assert hmi.hmi_pool_load_tenant(pool.h, 0, 0, [np.zeros(4, np.uint16)]) == hmi.HMI_ERR_SHAPE
     finally:
         pool.close()
+
+
+def test_a_pool_larger_than_the_gpu_is_refused_and_leaves_nothing_behind(hmi):
+    """6 000 slots of a 67 MB FFN block are 400 GB: creation fails with HMI_ERR_OOM, hands out no pool, gives back
+    what it had already allocated, and a pool of ordinary size is created and works right afterwards."""
+    torch.cuda.synchronize()
+    free_before, _ = torch.cuda.mem_get_info()
+    rc, h = hmi.hmi_pool_create(block=hmi.HMI_BLOCK_FFN, dtype=hmi.HMI_BF16, d_model=2048, d_ff=8192, n_heads=0,
+                                n_layers=1, max_tenants=6000, hbm_slots=6000, host_tier=0, max_requests=8,
+                                max_tokens=1024, ln_eps=1e-5, device=0,
+                                compute_stream=torch.cuda.current_stream().cuda_stream)
+    assert rc == hmi.HMI_ERR_OOM and h is None, (rc, hmi.hmi_last_error(None))
+    assert hmi.hmi_last_error(None)
+    free_after, _ = torch.cuda.mem_get_info()
+    assert abs(free_before - free_after) < (1 << 30), (free_before, free_after)
+    run_case(hmi, small(synth.BLOCK_FFN, "bf16"))
