@@ -74,8 +74,8 @@ typedef struct {
                            * element size must stay below 4 GiB (32-bit row offsets)      */
   int32_t d_ff;         /* FFN width, or adapter rank; multiple of 64 (bf16) / 16 (f32)   */
   int32_t n_heads;      /* attention blocks: d_model / n_heads must be 64; else 0         */
-  int32_t n_layers;     /* per-tenant layers held per tenant (>= 1)                       */
-  int32_t max_tenants;  /* tenant ids live in [0, max_tenants)                            */
+  int32_t n_layers;     /* per-tenant layers held per tenant (1 .. 1024)                  */
+  int32_t max_tenants;  /* tenant ids live in [0, max_tenants); at most 2^24              */
   int32_t hbm_slots;    /* tenants resident in HBM at once (<= max_tenants)               */
   int32_t host_tier;    /* 1: every loaded tenant also kept in pinned host memory; HBM is
                            an LRU cache over it, misses are copied in on a side stream    */

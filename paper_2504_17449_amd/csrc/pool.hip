@@ -14,6 +14,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <exception>
 #include <mutex>
 #include <new>
 #include <string>
@@ -26,7 +27,10 @@ namespace {
 constexpr int kRing = 8;
 constexpr size_t kAlign = 256;
 constexpr int kArenaImages = 32;  // pinned host images per hipHostMalloc call
+constexpr int kMaxTenantIds = 1 << 24;   // tenant id space of one pool
+constexpr int kMaxLayers = 1024;
 
+thread_local hmi_pool_t* g_in_creation = nullptr;   // the pool hmi_pool_create is building on this thread, if any
 thread_local char g_create_error[256] = "";   // why the calling thread's last hmi_pool_create failed
 
 // Limits of hmi_layer_forward_static and the layout of its routing arrays inside `scratch`.
@@ -256,6 +260,7 @@ enum { T_W1 = 0, T_B1, T_W2, T_B2, T_LNG, T_LNB };                      // FFN /
 enum { A_WQKV = 0, A_BQKV, A_WO, A_BO, A_LN1G, A_LN1B, A_W1, A_B1, A_W2, A_B2, A_LN2G, A_LN2B };
 
 void free_all(hmi_pool* p) {
+  if (g_in_creation == p) g_in_creation = nullptr;
   (void)hipStreamSynchronize(p->compute);
   if (p->copy) (void)hipStreamSynchronize(p->copy);
   (void)hipFree(p->d_pool);
@@ -377,7 +382,7 @@ int bits_for(int n) {
 
 extern "C" {
 
-int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
+static int32_t create_impl(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   if (!cfg || !out) return fail(nullptr, HMI_ERR_ARG, "null config or out pointer");
   const hmi_pool_config_t& c = *cfg;
   if (c.block < HMI_BLOCK_FFN || c.block > HMI_BLOCK_DEC_ADAPTER) return fail(nullptr, HMI_ERR_ARG, "bad block %d", c.block);
@@ -400,6 +405,9 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   }
   if (c.n_layers < 1 || c.max_tenants < 1 || c.hbm_slots < 1 || c.hbm_slots > c.max_tenants)
     return fail(nullptr, HMI_ERR_ARG, "need n_layers >= 1 and 1 <= hbm_slots <= max_tenants");
+  // per-tenant and per-(tenant, layer) host tables are made here: keep their sizes sane
+  if (c.max_tenants > kMaxTenantIds || c.n_layers > kMaxLayers)
+    return fail(nullptr, HMI_ERR_ARG, "max_tenants must be <= %d and n_layers <= %d", kMaxTenantIds, kMaxLayers);
   if (c.max_requests < 1 || c.max_requests > kMaxRequests || c.max_tokens < c.max_requests)
     return fail(nullptr, HMI_ERR_ARG, "need 1 <= max_requests <= %d and max_tokens >= max_requests", kMaxRequests);
   if (!c.host_tier && c.hbm_slots != c.max_tenants)
@@ -431,6 +439,12 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
   }
   p->image_bytes = off;
   p->slot_stride = off * c.n_layers;
+  // sizes are products of caller-given 32-bit numbers: refuse before any of them can wrap
+  if ((unsigned __int128)p->slot_stride * (unsigned)c.hbm_slots >= ((unsigned __int128)1 << 46)) {
+    delete p;
+    return fail(nullptr, HMI_ERR_OOM, "hbm_slots x n_layers x image bytes exceeds any device");
+  }
+  g_in_creation = p;   // from here on an exception handler or an error path gives everything back through free_all
   off = 0;
   for (auto& sh : shared_tensor_shapes(c)) {
     const size_t bytes = (size_t)sh.first * (sh.second ? sh.second : 1) * p->esize;
@@ -590,8 +604,18 @@ int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
     CREATE_TRY(hipMalloc(&p->w_yst, MT * d * es));
   }
 #undef CREATE_TRY
+  g_in_creation = nullptr;
   *out = p;
   return HMI_OK;
+}
+
+int32_t hmi_pool_create(const hmi_pool_config_t* cfg, hmi_pool_t** out) {
+  try {
+    return create_impl(cfg, out);
+  } catch (const std::exception& e) {   // a host table could not be allocated: nothing may cross the C boundary
+    if (g_in_creation) free_all(g_in_creation);
+    return fail(nullptr, HMI_ERR_OOM, "host allocation failed: %s", e.what());
+  }
 }
 
 int32_t hmi_pool_load_tenant(hmi_pool_t* p, int32_t tenant, int32_t layer,
@@ -1183,7 +1207,9 @@ int32_t hmi_kv_create(hmi_pool_t* p, int32_t max_seqs, int32_t max_len) {
   if (p->d_kv) return fail(p, HMI_ERR_ARG, "the pool already has a key/value cache");
   if (max_seqs < 1 || max_len < 1) return fail(p, HMI_ERR_ARG, "max_seqs and max_len must be positive");
   HIP_TRY(p, hipSetDevice(c.device));
-  const size_t bytes = (size_t)c.n_layers * max_seqs * 2 * (size_t)c.d_model * max_len * sizeof(uint16_t);
+  const unsigned __int128 wide = (unsigned __int128)c.n_layers * (unsigned)max_seqs * 2u * (unsigned)c.d_model * (unsigned)max_len * sizeof(uint16_t);
+  if (wide >= ((unsigned __int128)1 << 46)) return fail(p, HMI_ERR_OOM, "a key/value cache of that size exceeds any device");
+  const size_t bytes = (size_t)wide;
   HIP_TRY(p, hipMalloc(&p->d_kv, bytes));
   p->kv_seqs = max_seqs; p->kv_max_len = max_len;
   p->kv_len.assign(max_seqs, 0);

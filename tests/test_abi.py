@@ -38,6 +38,14 @@ def test_argument_errors_need_no_gpu():
     rc, h = pkg.hmi_pool_create(block=0, dtype=1, d_model=100, d_ff=64, max_tenants=1,
                                 max_requests=1, max_tokens=1)
     assert rc == pkg.HMI_ERR_ARG and "multiples" in pkg.hmi_last_error(None)
+    # sizes that are products of caller-given numbers are refused before anything is allocated or can wrap
+    small = dict(block=0, dtype=1, d_model=64, d_ff=64, max_tenants=1, max_requests=1, max_tokens=1)
+    for kw, want, word in ((dict(max_tenants=1 << 25, hbm_slots=1 << 25), pkg.HMI_ERR_ARG, "max_tenants"),
+                           (dict(n_layers=5000), pkg.HMI_ERR_ARG, "n_layers"),
+                           (dict(max_tenants=1 << 24, hbm_slots=1 << 24, n_layers=1024, d_model=2048, d_ff=1 << 20),
+                            pkg.HMI_ERR_OOM, "exceeds")):
+        rc, h = pkg.hmi_pool_create(**{**small, **kw})
+        assert rc == want and h is None and word in pkg.hmi_last_error(None), (kw, rc, pkg.hmi_last_error(None))
     # the other entry points with no pool: an error code, nothing touched, no GPU call
     for name in ("hmi_stack_forward", "hmi_stack_forward_f32"):
         assert getattr(pkg.lib, name)(None, 0, 1, None, None, None, None, 0) == pkg.HMI_ERR_ARG
