@@ -356,6 +356,64 @@ def test_loading_a_tenant_again_replaces_its_weights(host_tier):
         pool.close()
 
 
+@pytest.mark.parametrize("seed,dtype", [(0, "f32"), (3, "f32"), (10, "bf16")])
+def test_host_tier_random_operations_with_nothing_synchronised(seed, dtype):
+    """Eighty operations drawn from a seeded generator on a 5-slot cache over 24 tenant ids, two layers: forwards of up
+    to five distinct tenants, prefetches of up to eight (more than fit), tenants loaded again with other tenants'
+    weights, new ids created as aliases of loaded ones (also of aliases).  Nothing is synchronised until the end, so
+    copies, evictions and forwards of many calls are in flight together; every forward's output must be the oracle's
+    under the weights each tenant id held when the call was made."""
+    from paper_2504_17449_amd import harness
+    rng = np.random.default_rng(seed)
+    T, SLOTS, R, L = 24, 5, 7, 2
+    wl = synth.Workload("tier_random", synth.BLOCK_ENC_POSTLN, dtype, 64 if dtype == "f32" else 128, 128,
+                        1 if dtype == "f32" else 2, L, T, R, 1, 30, "uniform", 0.0, 1e-5, SLOTS, True, seed=100 + seed)
+    pool = harness.create_pool(wl, max_requests=R, max_tokens=R * 30)
+    holds = {}                      # tenant id -> the id whose generated weights it holds now
+    shares = set()                  # ids that share a pinned image (as alias or as source): these cannot be loaded again
+    runs = []
+    try:
+        harness.load_tenants(pool, wl, range(16))
+        holds.update({t: t for t in range(16)})
+        for it in range(80):
+            op = rng.choice(["forward", "forward", "forward", "prefetch", "load again", "alias"])
+            if op == "forward":
+                pick = rng.choice(sorted(holds), size=int(rng.integers(1, SLOTS + 1)), replace=False)
+                ids = rng.choice(pick, size=R).astype(np.int32)
+                _, lens, x = harness.batch_to_device(wl, it)
+                y = torch.empty_like(x)
+                pool.stack_forward(0, L, x, y, ids, lens)
+                runs.append((it, np.array([holds[int(t)] for t in ids], np.int32), lens, y))
+            elif op == "prefetch":
+                ids = rng.choice(sorted(holds), size=int(rng.integers(1, 9))).astype(np.int32)
+                for layer in range(L):
+                    pool.prefetch(layer, ids)
+            elif op == "load again":
+                own = [t for t in holds if t not in shares]
+                if own:
+                    t, src = int(rng.choice(own)), int(rng.integers(0, T))
+                    for layer in range(L):
+                        pool.load_tenant(t, layer, synth.tenant_storage(wl, src, layer))
+                    holds[t] = src
+            else:
+                free = [t for t in range(T) if t not in holds]
+                if free:
+                    t, src = int(rng.choice(free)), int(rng.choice(sorted(holds)))
+                    pool.alias_tenant(t, src)
+                    holds[t] = holds[src]
+                    shares.update((t, src))
+        torch.cuda.synchronize()
+        st = pool.stats()
+        print(f"  {len(runs)} forwards, {st}", flush=True)
+        assert len(runs) >= 30 and st["misses"] > 20 and st["evictions"] > 20
+        for it, weight_ids, lens, y in runs:
+            y_ref = oracle_forward(wl, weight_ids, lens, None, it)
+            max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, np.arange(len(y_ref)), dtype)
+            assert ok, (it, max_abs, rel)
+    finally:
+        pool.close()
+
+
 def test_host_tier_zipf_batches_with_prefetch_bf16():
     """The 10k-tenant recipe at reduced size: 1 500 tenants in pinned host memory behind a
     160-slot HBM cache, Zipf 0.8 popularity, ragged lengths, two layers.  Batch b+1 is
