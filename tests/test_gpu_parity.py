@@ -206,6 +206,19 @@ def test_bf16_adapter_rank_64(hmi):
     run_case(hmi, small(synth.BLOCK_ADAPTER, "bf16", d_model=768, d_ff=64, seq_max=128, seq_min=128))
 
 
+@pytest.mark.parametrize("block,kw", [
+    (synth.BLOCK_ADAPTER, dict(d_model=1024, d_ff=128)),
+    (synth.BLOCK_ADAPTER, dict(d_model=768, d_ff=64, n_layers=2)),
+    (synth.BLOCK_ENC_ADAPTER, dict(d_model=1024, d_ff=4096, n_heads=16, adapter_rank=128)),
+], ids=["adapter_d1024_rank128", "adapter_two_layers", "shared_layer_d1024_rank128"])
+def test_adapter_as_two_gemms(hmi, block, kw):
+    """Where the one-kernel adapter does not apply (d = 1024: its rows do not fit LDS twice; an adapter-only pool of
+    several layers: fp32 between the layers) the adapter runs as two grouped GEMMs; the up-projection has k = rank
+    = 64 or 128, below what the persistent kernel takes, so it goes to the general 256 x 256 kernel with direct-to-LDS
+    copies.  A few thousand rows (more than the small-batch kernel takes), every row compared."""
+    run_case(hmi, small(block, "bf16", n_tenants=12, hbm_slots=12, n_requests=40, seq_min=1, seq_max=300, **kw))
+
+
 def test_one_kernel_adapter_refuses_the_fp32_result_call(hmi):
     """The one-kernel adapter rounds as it stores: asking it for an fp32 result is an argument error, y untouched."""
     from paper_2504_17449_amd import harness
