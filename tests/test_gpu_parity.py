@@ -744,6 +744,31 @@ def test_two_host_threads_each_with_a_pool_of_its_own(hmi):
             assert ok, (wl.name, b, max_abs, rel)
 
 
+def test_tenant_ids_up_to_four_million(hmi):
+    """The router's radix sort takes as many passes of up to six bits as the id space needs: one for 64 tenants, two
+    for 1 000, three for 10 000.  An id space of 2^22 (host-tier pool, eight HBM slots) takes four; the few tenants
+    that exist have ids spread over the whole range, some equal in their low 6, 12 and 18 bits."""
+    from paper_2504_17449_amd import harness
+    T = 1 << 22
+    wl = small(synth.BLOCK_FFN, "bf16", n_tenants=T, hbm_slots=8, host_tier=True, n_requests=40, seq_max=40)
+    exist = np.array([3, 3 + (1 << 6), 3 + (1 << 12), 3 + (1 << 18), 70000, 1 << 20, T - 1], np.int32)
+    rng = np.random.default_rng(7)
+    ids = rng.choice(exist, size=wl.n_requests).astype(np.int32)
+    _, lens, x = harness.batch_to_device(wl, 0)
+    pool = harness.create_pool(wl, max_requests=len(ids), max_tokens=int(lens.sum()))
+    try:
+        harness.load_tenants(pool, wl, exist.tolist())
+        y = torch.empty_like(x)
+        pool.forward(0, x, y, ids, lens)
+        torch.cuda.synchronize()
+        check_route(pool, ids, lens)
+        y_ref = oracle_forward(wl, ids, lens, None, 0)
+        max_abs, rel, ok = compare(harness.device_to_f64(y), y_ref, np.arange(len(y_ref)), "bf16")
+        assert ok, (max_abs, rel)
+    finally:
+        pool.close()
+
+
 def test_single_request_and_single_tenant(hmi):
     run_case(hmi, small(synth.BLOCK_ENC_POSTLN, "bf16", n_requests=1, seq_min=5, seq_max=5))
     run_case(hmi, small(synth.BLOCK_DEC_PRELN, "bf16", n_tenants=1, hbm_slots=1, n_requests=9))
