@@ -769,6 +769,14 @@ def test_tenant_ids_up_to_four_million(hmi):
         pool.close()
 
 
+@pytest.mark.parametrize("block", [synth.BLOCK_ENC_POSTLN, synth.BLOCK_DEC_PRELN])
+def test_one_request_of_4096_tokens(hmi, block):
+    """One sequence of 4 096 tokens: 64 key blocks per query block in the attention kernel (32 query blocks of 128),
+    one segment of 16 m-tiles in the GEMMs; bidirectional and causal, every row compared."""
+    run_case(hmi, small(block, "bf16", d_model=256, d_ff=512, n_heads=4, n_tenants=1, hbm_slots=1, n_requests=1,
+                        seq_min=4096, seq_max=4096))
+
+
 def test_single_request_and_single_tenant(hmi):
     run_case(hmi, small(synth.BLOCK_ENC_POSTLN, "bf16", n_requests=1, seq_min=5, seq_max=5))
     run_case(hmi, small(synth.BLOCK_DEC_PRELN, "bf16", n_tenants=1, hbm_slots=1, n_requests=9))
