@@ -207,6 +207,8 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
   {
     const int tm0 = rt.tile_m[0], tm1 = rt.tile_m[1];
     int carry0 = 0, carry1 = 0;
+    int* tb0 = key[cur ^ 1];            // segment -> its first tile in list 0 / list 1 (the sort's spare buffers:
+    int* tb1 = val[cur ^ 1];            // the slots kept in the first one were last read a barrier ago)
     const int grounds = (G + kRouterThreads - 1) / kRouterThreads;
     for (int c = 0; c < grounds; ++c) {
       const int g = c * kRouterThreads + tid;
@@ -215,14 +217,28 @@ __global__ __launch_bounds__(kRouterThreads) void router_kernel(Route rt, int R,
       const int nt0 = tm0 > 0 ? (rows + tm0 - 1) / tm0 : 0, nt1 = tm1 > 0 ? (rows + tm1 - 1) / tm1 : 0;
       int base0, base1, tot0, tot1;
       block_exscan2(nt0, nt1, wave_tot, base0, base1, tot0, tot1);
-      base0 += carry0; base1 += carry1;
-      for (int t = 0; t < nt0; ++t) { rt.tile_seg[0][base0 + t] = g; rt.tile_row0[0][base0 + t] = first + t * tm0; }
-      for (int t = 0; t < nt1; ++t) { rt.tile_seg[1][base1 + t] = g; rt.tile_row0[1][base1 + t] = first + t * tm1; }
+      if (g < G) { tb0[g] = base0 + carry0; tb1[g] = base1 + carry1; }
       carry0 += tot0; carry1 += tot1;
     }
     if (tid == 0) {
       if (tm0 > 0) rt.n_tiles[0][0] = carry0;
       if (tm1 > 0) rt.n_tiles[1][0] = carry1;
+    }
+    __syncthreads();
+    // one thread per tile, whatever the sizes of the segments (a single tenant's batch is one segment of hundreds of
+    // tiles): the tile's segment is the last one whose first tile is not behind it
+    for (int k = 0; k < 2; ++k) {
+      const int* tb = k == 0 ? tb0 : tb1;
+      const int tm = k == 0 ? tm0 : tm1, n = k == 0 ? carry0 : carry1;
+      for (int t = tid; t < n; t += kRouterThreads) {
+        int lo = 0, hi = G - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (tb[mid] <= t) lo = mid; else hi = mid - 1;
+        }
+        rt.tile_seg[k][t] = lo;
+        rt.tile_row0[k][t] = segtok_s[lo] + (t - tb[lo]) * tm;
+      }
     }
   }
 
