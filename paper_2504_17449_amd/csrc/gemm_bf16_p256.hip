@@ -124,6 +124,10 @@ __device__ __forceinline__ int perm_w(int i) { return ((i >> 2) & 1) * 16 + (i >
 #warning "gemm_bf16_p256: timing-only ablation build, results are wrong"
 #endif
 
+// Results leave with the non-temporal hint: nothing in this launch reads them again, and every line of L2 they do not
+// take stays with the operand panels that other workgroups of the XCD are about to ask for (measured: 1-2 % fewer
+// bytes fetched, GEMM time -0.7 to -1 % on the FFN, encoder and shared-layer workloads).
+#define HMI_STORE_OUT(PTR, V) __builtin_nontemporal_store((V), (PTR))
 #define HMI_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 #define HMI_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
@@ -489,13 +493,13 @@ void gemm_bf16_p256_kernel(GemmArgs g, Route rt, int total, int per_xcd) {
                   }
                 }
                 const u32x2 hh = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-                if (OUT_F32) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + off) = v;
-                else *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C) + off) = hh;
-                if (HAS_C2) *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C2) + off) = hh;
+                if (OUT_F32) HMI_STORE_OUT(reinterpret_cast<f32x4*>(reinterpret_cast<float*>(g.C) + off), v);
+                else HMI_STORE_OUT(reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C) + off), hh);
+                if (HAS_C2) HMI_STORE_OUT(reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(g.C2) + off), hh);
               } else {
                 const u32x4 h = *reinterpret_cast<const u32x4*>(rrow + ((c ^ (r & 15)) << 4));
-                *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C) + off) = h;
-                if (HAS_C2) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C2) + off) = h;
+                HMI_STORE_OUT(reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C) + off), h);
+                if (HAS_C2) HMI_STORE_OUT(reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(g.C2) + off), h);
               }
             }
           }

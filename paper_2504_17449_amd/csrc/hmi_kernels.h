@@ -108,6 +108,7 @@ struct AdapterArgs {
   size_t wd_off, bd_off, wu_off, bu_off;  // byte offsets inside a slot (layer included)
   int d;
   int which_tiles, n_tiles128;        // index and length of the list of 128-row m-tiles
+  int stream_out;                     // 1: Y is not read again soon (the caller's result): stored with the non-temporal hint
 };
 bool adapter_bf16_supported(int d, int rank);
 void launch_adapter_bf16(const AdapterArgs& a, const Route& rt, hipStream_t s);

@@ -1117,6 +1117,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
           a.wd_off = lay + p->tl[T_W1].off; a.bd_off = lay + p->tl[T_B1].off;
           a.wu_off = lay + p->tl[T_W2].off; a.bu_off = lay + p->tl[T_B2].off;
           a.d = d; a.which_tiles = 1; a.n_tiles128 = n_mtiles[1];
+          a.stream_out = 1;
           ProfSpan ps(p, HMI_KERNEL_GEMM);
           launch_adapter_bf16(a, rt, s);
           break;
@@ -1311,6 +1312,7 @@ int32_t hmi_layer_forward_static(hmi_pool_t* p, int32_t layer, const void* x, vo
   a.wd_off = p->tl[T_W1].off; a.bd_off = p->tl[T_B1].off;
   a.wu_off = p->tl[T_W2].off; a.bu_off = p->tl[T_B2].off;
   a.d = c.d_model; a.which_tiles = 1; a.n_tiles128 = n_tiles128;
+  a.stream_out = 1;
   launch_adapter_bf16(a, rt, s);
   const uint64_t seq = p->fwd_done.record(s);
   for (int t : p->distinct) p->slot_fwd[p->slot_of_tenant[t]] = seq;
