@@ -86,8 +86,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(KvArgs a, Route rt) {
 #pragma unroll
     for (int u = 0; u < PB; ++u) {
       const int p = min(p0 + 32 * u, pos - 1);  // surplus positions of the last trip repeat a valid one and get no weight
-      kk[u] = *reinterpret_cast<const u16x8*>(Kc + (size_t)p * DH + part * 8);
-      vv[u] = *reinterpret_cast<const u16x8*>(Vc + (size_t)p * DH + part * 8);
+      // read once per step and far larger than the caches: the non-temporal hint keeps the lines out of L2, where the
+      // step's other kernels find their weights again (a step through six shared layers: 0.662 -> 0.601 ms)
+      kk[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Kc + (size_t)p * DH + part * 8));
+      vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x8*>(Vc + (size_t)p * DH + part * 8));
     }
     float sc[PB];
 #pragma unroll
