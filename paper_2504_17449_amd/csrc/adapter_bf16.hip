@@ -55,6 +55,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// A tenant's matrices.  In a decode step a tenant has a row or two: its 0.2 MB are read by one workgroup, once, and only push
+// the shared layers' weights out of the L2s (with the hint a step through six shared layers is 3 % shorter); over a full batch
+// the workgroups that hold the tenant's other rows read them again, from L2, and there the plain load is the faster one.
+template <bool ONCE>
+__device__ __forceinline__ bf16x8 load_w(const bf16x8* p) {
+  if (ONCE) return __builtin_nontemporal_load(p);
+  return *p;
+}
+
 template <int NV>
 struct Shape {
   static constexpr int CH = NV * 32;          // 16-byte chunks of a row (d = 256 NV)
@@ -75,7 +84,9 @@ struct Shape {
 //   row buffer   row r, position p holds the row's chunk p ^ (r & 15)
 //   partial sum  [kq][row r][16 chunks of 4 fp32], chunk q at position q ^ (r & 15)
 //   bottleneck   row r is 128 bytes (64 bf16), chunk c at position c ^ ((r >> 1) & 7)
-template <int NV>
+// ONCE: the tenants' matrices are loaded with the non-temporal hint (load_w above); STREAM: so are the result's stores.
+// Both are compile-time: a run-time choice between a hinted and a plain access to one address is merged into the plain one.
+template <int NV, bool ONCE, bool STREAM>
 __global__ __launch_bounds__(NTH) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void adapter_bf16_kernel(AdapterArgs a, Route rt) {
   using S = Shape<NV>;
@@ -150,7 +161,7 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
     const bf16x8* pwd = reinterpret_cast<const bf16x8*>(a.pool + (size_t)(SLOT) * a.slot_stride + a.wd_off) + \
                         ((cb * S::KS + 2 * kq) * 64 + lane);                                       \
     _Pragma("unroll") for (int s = 0; s < S::KSW; ++s)                                             \
-      wd[s] = pwd[((s >> 1) * 8 + (s & 1)) * 64];   /* k-step 8 (s / 2) + 2 kq + s % 2 */          \
+      wd[s] = load_w<ONCE>(pwd + ((s >> 1) * 8 + (s & 1)) * 64);   /* k-step 8 (s / 2) + 2 kq + s % 2 */ \
   }
 #define HMI_LOAD_BD(SLOT)                                                                          \
   {                                                                                                \
@@ -162,7 +173,7 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
     const char* base = a.pool + (size_t)(SLOT) * a.slot_stride;                                    \
     const bf16x8* pwu = reinterpret_cast<const bf16x8*>(base + a.wu_off) + (wave * NV * 4 * 64 + lane); \
     _Pragma("unroll") for (int c = 0; c < NV; ++c)                                                 \
-      _Pragma("unroll") for (int s = 0; s < 4; ++s) wu[c][s] = pwu[(c * 4 + s) * 64];              \
+      _Pragma("unroll") for (int s = 0; s < 4; ++s) wu[c][s] = load_w<ONCE>(pwu + (c * 4 + s) * 64); \
     _Pragma("unroll") for (int c = 0; c < NV; ++c) {                                               \
       const u32x4* pb = reinterpret_cast<const u32x4*>(base + a.bu_off + ((wave * NV + c) * 32 + h * 16) * 2); \
       bu[c][0] = pb[0]; bu[c][1] = pb[1];                                                          \
@@ -278,7 +289,7 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
             u32x4* dst = reinterpret_cast<u32x4*>(Y + (size_t)orow[r3] * S::ROWB + (sw[r3] ^ ((g & 1) << 7)));
             // a result that goes to the caller leaves without taking lines of L2 (the adapter-only block: 4.7 -> 5.0 TB/s);
             // inside a shared layer the next kernel reads it at once, and there the plain store is the faster one
-            if (a.stream_out) __builtin_nontemporal_store(v[r3], dst); else *dst = v[r3];
+            if (STREAM) __builtin_nontemporal_store(v[r3], dst); else *dst = v[r3];
           }
       }
     } else if (i + 1 < m) {
@@ -296,7 +307,8 @@ void adapter_bf16_kernel(AdapterArgs a, Route rt) {
 template <int NV>
 void launch_nv(const AdapterArgs& a, const Route& rt, hipStream_t s) {
   using S = Shape<NV>;
-  auto kern = adapter_bf16_kernel<NV>;
+  auto kern = a.stream_out ? adapter_bf16_kernel<NV, false, true>
+                           : a.weights_once ? adapter_bf16_kernel<NV, true, false> : adapter_bf16_kernel<NV, false, false>;
   const int n_cu = rt.n_cu >= 1 ? rt.n_cu : 256;
   const long long U = (long long)a.n_tiles128 * 4;
   if (U <= 0) return;
@@ -308,7 +320,11 @@ void launch_nv(const AdapterArgs& a, const Route& rt, hipStream_t s) {
 
 template <int NV>
 void allow_lds() {
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(adapter_bf16_kernel<NV>), hipFuncAttributeMaxDynamicSharedMemorySize,
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(adapter_bf16_kernel<NV, false, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            Shape<NV>::LDS);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(adapter_bf16_kernel<NV, true, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            Shape<NV>::LDS);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(adapter_bf16_kernel<NV, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             Shape<NV>::LDS);
 }
 

@@ -109,6 +109,7 @@ struct AdapterArgs {
   int d;
   int which_tiles, n_tiles128;        // index and length of the list of 128-row m-tiles
   int stream_out;                     // 1: Y is not read again soon (the caller's result): stored with the non-temporal hint
+  int weights_once;                   // 1: a tenant's matrices are read by about one unit of rows (a decode step): loaded with the non-temporal hint
 };
 bool adapter_bf16_supported(int d, int rank);
 void launch_adapter_bf16(const AdapterArgs& a, const Route& rt, hipStream_t s);

@@ -1096,6 +1096,7 @@ static int32_t forward_impl(hmi_pool_t* p, int32_t layer_begin, int32_t layer_en
         a.wd_off = lay + p->tl[T_W1].off; a.bd_off = lay + p->tl[T_B1].off;
         a.wu_off = lay + p->tl[T_W2].off; a.bu_off = lay + p->tl[T_B2].off;
         a.d = d; a.which_tiles = 1; a.n_tiles128 = n_mtiles[1];
+        a.weights_once = (long long)N <= 32LL * n_mtiles[1];
         ProfSpan ps(p, HMI_KERNEL_GEMM);
         launch_adapter_bf16(a, rt, s);
       } else {
