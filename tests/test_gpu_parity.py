@@ -375,13 +375,15 @@ def check_heads(pool, wl, ids, lens, x, X64):
     assert torch.equal(labels, labels2)
 
 
-@pytest.mark.parametrize("dtype,d_model", [("bf16", 128), ("bf16", 768), ("f32", 64)])
-def test_output_heads_ragged(hmi, dtype, d_model):
+@pytest.mark.parametrize("dtype,d_model,max_classes", [("bf16", 128, 9), ("bf16", 768, 9), ("f32", 64, 9),
+                                                       ("bf16", 2048, 64), ("f32", 528, 2)])
+def test_output_heads_ragged(hmi, dtype, d_model, max_classes):
     """Sec. 3.3.2: per-tenant linear heads with their own class counts, classification tenants on
-    the first row of a request, tagging tenants on every row, label = highest score."""
+    the first row of a request, tagging tenants on every row, label = highest score.  The last two cases: the
+    widest model with the most classes a head may have (64), and two classes on a width that is no multiple of 64."""
     from paper_2504_17449_amd import harness
     wl = small(synth.BLOCK_ADAPTER, dtype, d_model=d_model, d_ff=64 if dtype == "bf16" else 16, n_tenants=40,
-               hbm_slots=40, n_requests=60, seq_max=70, max_classes=9)
+               hbm_slots=40, n_requests=60, seq_max=70, max_classes=max_classes)
     ids, lens, x = harness.batch_to_device(wl)
     pool = harness.create_pool(wl, max_tokens=int(lens.sum()))
     try:
